@@ -1,0 +1,192 @@
+/*
+ * realb.h -- C ABI of the ReaLB rank-layer library for AMD MI355X (gfx950).
+ *
+ * One expert-parallel (EP) rank's MoE layer whose GEMM precision (BF16 or FP4)
+ * is chosen at run time from the router's statistics, following
+ *   "ReaLB: Real-Time Load Balancing for Multimodal MoE Inference"
+ *   (Sec. "Methodology": System Overview stages 1-4, Real-time Modality-aware LB
+ *   Scheduling, Overhead-Aware Pipeline Orchestration; Appendix "Implementation
+ *   Details": Quantization Details).
+ *
+ * Conventions for every entry point
+ *   - Pointers are DEVICE pointers unless the parameter name ends in _host.
+ *   - All tensors are dense, row-major, allocated and owned by the caller; the
+ *     library never frees or reallocates caller memory and never writes to the
+ *     weight tensors.  The only memory the library allocates is the context's
+ *     workspace, in realb_create, freed in realb_destroy.
+ *   - BF16 tensors are passed as void* to 16-bit patterns.
+ *   - FP4 tensors are OCP MXFP4: 4-bit E2M1 codes (bit 3 sign; magnitudes
+ *     0,.5,1,1.5,2,3,4,6), two per byte with the even element in the low nibble,
+ *     plus one E8M0 scale byte (2^(byte-127)) per block of 32 consecutive elements
+ *     along the contraction dimension.  The paper's NVFP4 (blocks of 16, E4M3
+ *     scale, global scale) is mapped onto this format because gfx950's
+ *     block-scaled matrix instructions take E8M0 scales.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *     are asynchronous on that stream unless stated otherwise.
+ *   - Return value: REALB_OK or a negative error code; realb_last_error() gives
+ *     the message of the calling thread's last failure.  Nothing aborts or throws.
+ *     Non-finite inputs are outside the contract.
+ *   - Shapes: H and I multiples of 128; E a multiple of D; 1 <= k <= min(E, 16);
+ *     E <= 512; n_local = E/D <= 64.  Expert e lives on rank e / n_local.
+ */
+#ifndef REALB_H
+#define REALB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct realb_ctx realb_ctx;
+
+enum { REALB_OK = 0, REALB_EINVAL = -1, REALB_ESHAPE = -2, REALB_ECAP = -3, REALB_EHIP = -4 };
+enum { REALB_BF16 = 0, REALB_FP4 = 1 };
+enum { REALB_FORCE_NONE = -1 };
+
+/* Layer shape and policy constants (paper Sec. "Setup": C = 1, M initially 0.9,
+ * tau = 1.5, Gamma = 2048; AIMD factors of the AIMD equation: 0.5 and +0.1). */
+typedef struct {
+    int T_max;          /* largest token count of any call */
+    int E, k, D;        /* routed experts, experts per token, EP ranks */
+    int H, I;           /* hidden size, SwiGLU intermediate size */
+    double C;           /* hotspot threshold on IB_d */
+    double tau;         /* congestion threshold on IB_global */
+    double M_init;      /* initial vision-ratio threshold M */
+    double aimd_mul;    /* multiplicative decrease factor */
+    double aimd_add;    /* additive increase step (result capped at 1) */
+    long long Gamma;    /* LB gate: policy active only if T > Gamma */
+    int aimd_enabled;   /* 0: M stays fixed (the fixed-threshold variants) */
+    int update_first;   /* 1: update M from this layer's IB_global, then decide */
+} realb_config;
+
+/* Fills *cfg with the paper's constants for the given shape. */
+void realb_default_config(realb_config* cfg, int T_max, int E, int k, int D, int H, int I);
+
+/* Creates a context: validates the shape, allocates the device workspace (sized
+ * from T_max, k, E, D) and pinned host staging, sets M = M_init.  Uses the
+ * current HIP device.  REALB_ESHAPE for unsupported shapes. */
+int realb_create(const realb_config* cfg, realb_ctx** out);
+int realb_destroy(realb_ctx* ctx);
+const char* realb_last_error(void);
+
+/* The AIMD threshold M carried across layers (host scalar). */
+double realb_get_M(const realb_ctx* ctx);
+int realb_set_M(realb_ctx* ctx, double M);
+
+/* Stage 1, routing and profiling (Sec. "System Overview"; runtime state of Sec.
+ * "Real-time Modality-aware LB Scheduling").
+ *   logits     f32 [T,E]      router logits
+ *   is_vision  u8  [T]        1 = vision token
+ *   topk_ids   i32 [T,k]  out experts in order of descending logit (ties: lower index)
+ *   topk_w     f32 [T,k]  out softmax over the k selected logits
+ *   expert_cnt i32 [E]    out assignments per expert
+ *   expert_vis i32 [E]    out of those, assignments of vision tokens
+ *   rank_load  i32 [D]    out Load_d = assignments on rank d
+ *   rank_vis   i32 [D]    out N_vd   = vision assignments on rank d
+ * T may be 0 (all counts 0).  REALB_ECAP if T > T_max. */
+int realb_route_stats(realb_ctx* ctx, const float* logits, const uint8_t* is_vision, int T,
+                      int32_t* topk_ids, float* topk_w, int32_t* expert_cnt, int32_t* expert_vis,
+                      int32_t* rank_load, int32_t* rank_vis, void* stream);
+
+/* Stage 2, modality-aware LB scheduling: LB gate (T > Gamma), AIMD update of M,
+ * hotspot set {d : IB_d > C}, FP4 iff hotspot and R_vd > M (Sec. "Real-time
+ * Modality-aware LB Scheduling", "LB Gate").  force = REALB_BF16 / REALB_FP4
+ * overrides the policy for every rank and leaves M untouched.
+ * Copies rank_load / rank_vis (device, [D]) to the host and SYNCHRONISES the
+ * stream; evaluates the policy on the host; updates the context's M.
+ *   prec_host [D] out, ib_global_host / M_after_host: optional (may be NULL). */
+int realb_select_precision(realb_ctx* ctx, const int32_t* rank_load, const int32_t* rank_vis, int T,
+                           int force, int32_t* prec_host, double* ib_global_host, double* M_after_host,
+                           void* stream);
+
+/* The same policy as a pure host function (no GPU, no context): all pointers are
+ * host pointers; *M_inout is read and updated. */
+int realb_select_precision_host(const realb_config* cfg, const int32_t* rank_load_host,
+                                const int32_t* rank_vis_host, int T, int force, double* M_inout,
+                                int32_t* prec_host, double* ib_global_host);
+
+/* Stage 3, on-the-fly precision transformation of this rank's expert weights
+ * (Sec. "Overhead-Aware Pipeline Orchestration", Overlapping Pipeline): BF16 ->
+ * MXFP4, blocks of 32 along the contraction dimension.  Weights are only read.
+ *   w13  bf16 [n_local, 2I, H]  rows [0,I) gate, [I,2I) up     -> w13_q u8 [n_local,2I,H/2], w13_s u8 [n_local,2I,H/32]
+ *   w2   bf16 [n_local, H, I]                                   -> w2_q  u8 [n_local,H,I/2],  w2_s  u8 [n_local,H,I/32]
+ * Meant to be issued on a side stream so that it overlaps realb_permute. */
+int realb_quantize_experts_fp4(realb_ctx* ctx, const void* w13, const void* w2, int n_local,
+                               uint8_t* w13_q, uint8_t* w13_s, uint8_t* w2_q, uint8_t* w2_s, void* stream);
+
+/* The same encoder on any BF16 matrix [rows, K] (K multiple of 32): q u8 [rows,K/2],
+ * s u8 [rows,K/32].  No context needed. */
+int realb_quantize_rows_fp4(const void* x, long long rows, int K, uint8_t* q, uint8_t* s, void* stream);
+
+/* Token permutation / dispatch packing for rank `rank` (the local stand-in for
+ * the all-to-all dispatch of Sec. "Overhead-Aware Pipeline Orchestration").
+ * Rows are this rank's assignments sorted by (local expert, a = t*k + j).
+ *   x              bf16 [T,H]
+ *   topk_ids       i32  [T,k]
+ *   expert_offsets i32  [n_local+1] out  exclusive prefix of local expert counts
+ *   row_to_assign  i32  [>= R]      out  a of each row (R = expert_offsets[n_local])
+ *   assign_to_row  i32  [T*k]       out  row of each assignment, -1 if not local
+ *   prec == REALB_BF16: x_perm bf16 [>= R, H] out  (x_q, x_s ignored, may be NULL)
+ *   prec == REALB_FP4 : x_q u8 [>= R, H/2], x_s u8 [>= R, H/32] out (x_perm ignored)
+ * Row buffers must hold max_rows rows; REALB_EINVAL if max_rows < min(T*k, T*n_local)
+ * (the worst case), since R is only known on the device. */
+int realb_permute(realb_ctx* ctx, const void* x, const int32_t* topk_ids, int T, int rank, int prec,
+                  long long max_rows, int32_t* expert_offsets, int32_t* row_to_assign, int32_t* assign_to_row,
+                  void* x_perm, uint8_t* x_q, uint8_t* x_s, void* stream);
+
+/* Stage 4, balanced MoE execution: SwiGLU expert FFN as two grouped GEMMs over
+ * the expert segments given by expert_offsets (read on the device).
+ *   gate/up: G,U = X . W13^T (FP32 accumulate), h = silu(G)*U, h rounded to BF16;
+ *            FP4 path: that BF16 h is encoded to MXFP4 along I (W4A4).
+ *   down:    Y = h . W2^T (FP32 accumulate), rounded to BF16.
+ *   prec == REALB_BF16: x = x_perm bf16 [max_rows,H], w13/w2 = BF16 weights, x_s/w13_s/w2_s ignored,
+ *                       h_mid bf16 [max_rows,I] (workspace/out), h_s ignored
+ *   prec == REALB_FP4 : x = x_q, w13 = w13_q, w2 = w2_q with their scale tensors,
+ *                       h_mid u8 [max_rows,I/2], h_s u8 [max_rows,I/32] (workspace/out)
+ *   y_rows bf16 [max_rows,H] out; only rows < R are written. */
+int realb_grouped_moe_ffn(realb_ctx* ctx, int prec, const int32_t* expert_offsets, int n_local,
+                          long long max_rows, const void* x, const uint8_t* x_s,
+                          const void* w13, const uint8_t* w13_s, const void* w2, const uint8_t* w2_s,
+                          void* h_mid, uint8_t* h_s, void* y_rows, void* stream);
+
+/* Unpermute + weighted combine (local part of the result combination):
+ * out[t] = sum over j with assign_to_row[t*k+j] >= 0 of topk_w[t,j] * y_rows[row],
+ * FP32 accumulate in order of j, rounded once to BF16; tokens with no local
+ * expert give 0.   out bf16 [T,H]. */
+int realb_combine(realb_ctx* ctx, const void* y_rows, const int32_t* assign_to_row, const float* topk_w,
+                  int T, void* out, void* stream);
+
+/* All tensors of one layer call, for realb_layer_forward. */
+typedef struct {
+    /* inputs */
+    const float* logits; const uint8_t* is_vision; const void* x; int T;
+    const void* w13; const void* w2;            /* this rank's BF16 expert weights */
+    int rank; int force; int overlap;           /* overlap != 0: weight encoding on the context's side stream */
+    long long max_rows;
+    /* outputs / workspaces (caller-allocated) */
+    int32_t* topk_ids; float* topk_w; int32_t* expert_cnt; int32_t* expert_vis;
+    int32_t* rank_load; int32_t* rank_vis;
+    int32_t* expert_offsets; int32_t* row_to_assign; int32_t* assign_to_row;
+    void* x_perm; uint8_t* x_q; uint8_t* x_s;
+    uint8_t* w13_q; uint8_t* w13_s; uint8_t* w2_q; uint8_t* w2_s;
+    void* h_mid; uint8_t* h_s; void* y_rows; void* out;
+    /* results (host) */
+    int32_t prec_host[64]; double ib_global; double M_after;
+} realb_layer_io;
+
+/* Runs the whole path for one rank on `stream`: route_stats -> select_precision
+ * (host decision, one stream sync) -> [FP4 only: quantize_experts_fp4, on the
+ * context's side stream when io->overlap, concurrent with] permute ->
+ * grouped_moe_ffn -> combine.  The side stream is joined before the GEMMs. */
+int realb_layer_forward(realb_ctx* ctx, realb_layer_io* io, void* stream);
+
+/* Runs permute .. combine for one rank with a precision already decided and
+ * routing already computed (used to time simulated ranks one after the other). */
+int realb_rank_forward(realb_ctx* ctx, realb_layer_io* io, int prec, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REALB_H */

@@ -1,0 +1,45 @@
+// Internal declarations shared by the library's translation units (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdarg.h>
+#include "../../include/realb.h"
+
+namespace realb {
+
+constexpr int kWave = 64;
+constexpr int kPermChunk = 1024;   // assignments ranked by one wave in permute
+
+struct Ctx {
+    realb_config cfg;
+    int n_local;
+    int device;
+    double M;
+    // device workspace
+    int32_t* wave_cnt;     // [n_chunks_max, n_local]  per-chunk local-expert counts, then exclusive bases
+    int n_chunks_max;
+    // pinned host staging for the policy's inputs
+    int32_t* stats_host;   // [2*D]
+    hipStream_t side;      // side stream for the weight encoder
+    hipEvent_t ev_fork, ev_join;
+};
+
+void set_error(const char* fmt, ...);
+int hip_fail(hipError_t e, const char* what);
+
+#define REALB_HIP(call)                                                        \
+    do {                                                                       \
+        hipError_t e__ = (call);                                               \
+        if (e__ != hipSuccess) return ::realb::hip_fail(e__, #call);           \
+    } while (0)
+
+#define REALB_REQUIRE(cond, code, ...)                                         \
+    do {                                                                       \
+        if (!(cond)) { ::realb::set_error(__VA_ARGS__); return (code); }       \
+    } while (0)
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }
+
+}  // namespace realb

@@ -1,0 +1,55 @@
+// The rank layer end to end: the paper's four-stage pipeline (Sec. "System
+// Overview") with the weight transformation overlapped with dispatch packing
+// (Sec. "Overhead-Aware Pipeline Orchestration"): the encoder runs on the
+// context's side stream while the permutation runs on the caller's stream, and
+// is joined before the GEMMs.
+#include "common.h"
+
+using namespace realb;
+
+extern "C" int realb_rank_forward(realb_ctx* ctx, realb_layer_io* io, int prec, void* stream) {
+    REALB_REQUIRE(ctx && io, REALB_EINVAL, "NULL argument");
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    REALB_REQUIRE(prec == REALB_BF16 || prec == REALB_FP4, REALB_EINVAL, "bad precision %d", prec);
+    hipStream_t s = as_stream(stream);
+    int rc;
+    const bool fp4 = prec == REALB_FP4;
+    if (fp4) {
+        REALB_REQUIRE(io->w13_q && io->w13_s && io->w2_q && io->w2_s, REALB_EINVAL, "NULL FP4 weight buffer");
+        if (io->overlap) {
+            REALB_HIP(hipEventRecord(c->ev_fork, s));
+            REALB_HIP(hipStreamWaitEvent(c->side, c->ev_fork, 0));
+            rc = realb_quantize_experts_fp4(ctx, io->w13, io->w2, c->n_local, io->w13_q, io->w13_s, io->w2_q, io->w2_s, c->side);
+            if (rc != REALB_OK) return rc;
+            REALB_HIP(hipEventRecord(c->ev_join, c->side));
+        } else {
+            rc = realb_quantize_experts_fp4(ctx, io->w13, io->w2, c->n_local, io->w13_q, io->w13_s, io->w2_q, io->w2_s, stream);
+            if (rc != REALB_OK) return rc;
+        }
+    }
+    rc = realb_permute(ctx, io->x, io->topk_ids, io->T, io->rank, prec, io->max_rows, io->expert_offsets, io->row_to_assign,
+                       io->assign_to_row, io->x_perm, io->x_q, io->x_s, stream);
+    if (rc != REALB_OK) return rc;
+    if (fp4 && io->overlap) REALB_HIP(hipStreamWaitEvent(s, c->ev_join, 0));
+    if (fp4)
+        rc = realb_grouped_moe_ffn(ctx, prec, io->expert_offsets, c->n_local, io->max_rows, io->x_q, io->x_s, io->w13_q,
+                                   io->w13_s, io->w2_q, io->w2_s, io->h_mid, io->h_s, io->y_rows, stream);
+    else
+        rc = realb_grouped_moe_ffn(ctx, prec, io->expert_offsets, c->n_local, io->max_rows, io->x_perm, nullptr, io->w13,
+                                   nullptr, io->w2, nullptr, io->h_mid, nullptr, io->y_rows, stream);
+    if (rc != REALB_OK) return rc;
+    return realb_combine(ctx, io->y_rows, io->assign_to_row, io->topk_w, io->T, io->out, stream);
+}
+
+extern "C" int realb_layer_forward(realb_ctx* ctx, realb_layer_io* io, void* stream) {
+    REALB_REQUIRE(ctx && io, REALB_EINVAL, "NULL argument");
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    REALB_REQUIRE(io->rank >= 0 && io->rank < c->cfg.D, REALB_EINVAL, "rank=%d outside [0,%d)", io->rank, c->cfg.D);
+    int rc = realb_route_stats(ctx, io->logits, io->is_vision, io->T, io->topk_ids, io->topk_w, io->expert_cnt, io->expert_vis,
+                               io->rank_load, io->rank_vis, stream);
+    if (rc != REALB_OK) return rc;
+    rc = realb_select_precision(ctx, io->rank_load, io->rank_vis, io->T, io->force, io->prec_host, &io->ib_global,
+                                &io->M_after, stream);
+    if (rc != REALB_OK) return rc;
+    return realb_rank_forward(ctx, io, io->prec_host[io->rank], stream);
+}
