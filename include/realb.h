@@ -26,7 +26,7 @@
  *   - Return value: REALB_OK or a negative error code; realb_last_error() gives
  *     the message of the calling thread's last failure.  Nothing aborts or throws.
  *     Non-finite inputs are outside the contract.
- *   - Shapes: H and I multiples of 128; E a multiple of D; 1 <= k <= min(E, 16);
+ *   - Shapes: H and I multiples of 128, H <= 8192; E a multiple of D; 1 <= k <= min(E, 16);
  *     E <= 512; n_local = E/D <= 64.  Expert e lives on rank e / n_local.
  */
 #ifndef REALB_H
@@ -150,6 +150,16 @@ int realb_grouped_moe_ffn(realb_ctx* ctx, int prec, const int32_t* expert_offset
                           long long max_rows, const void* x, const uint8_t* x_s,
                           const void* w13, const uint8_t* w13_s, const void* w2, const uint8_t* w2_s,
                           void* h_mid, uint8_t* h_s, void* y_rows, void* stream);
+
+/* The two GEMMs of realb_grouped_moe_ffn as separate calls (same arguments and
+ * layouts): gate/up writes h_mid (and h_s), down reads them and writes y_rows.
+ * realb_grouped_moe_ffn is exactly gate_up followed by down on the same stream. */
+int realb_grouped_moe_ffn_gate_up(realb_ctx* ctx, int prec, const int32_t* expert_offsets, int n_local,
+                                  long long max_rows, const void* x, const uint8_t* x_s,
+                                  const void* w13, const uint8_t* w13_s, void* h_mid, uint8_t* h_s, void* stream);
+int realb_grouped_moe_ffn_down(realb_ctx* ctx, int prec, const int32_t* expert_offsets, int n_local,
+                               long long max_rows, const void* h_mid, const uint8_t* h_s,
+                               const void* w2, const uint8_t* w2_s, void* y_rows, void* stream);
 
 /* Unpermute + weighted combine (local part of the result combination):
  * out[t] = sum over j with assign_to_row[t*k+j] >= 0 of topk_w[t,j] * y_rows[row],

@@ -14,8 +14,8 @@ _LIB = None
 EXPORTS = [
     "realb_default_config", "realb_create", "realb_destroy", "realb_last_error", "realb_get_M", "realb_set_M",
     "realb_route_stats", "realb_select_precision", "realb_select_precision_host", "realb_quantize_experts_fp4",
-    "realb_quantize_rows_fp4", "realb_permute", "realb_grouped_moe_ffn", "realb_combine", "realb_layer_forward",
-    "realb_rank_forward",
+    "realb_quantize_rows_fp4", "realb_permute", "realb_grouped_moe_ffn", "realb_grouped_moe_ffn_gate_up",
+    "realb_grouped_moe_ffn_down", "realb_combine", "realb_layer_forward", "realb_rank_forward",
 ]
 
 
@@ -74,6 +74,8 @@ def load_library() -> C.CDLL:
     lib.realb_quantize_rows_fp4.argtypes = [vp, C.c_longlong, C.c_int, vp, vp, vp]
     lib.realb_permute.argtypes = [vp, vp, vp, C.c_int, C.c_int, C.c_int, C.c_longlong, vp, vp, vp, vp, vp, vp, vp]
     lib.realb_grouped_moe_ffn.argtypes = [vp, C.c_int, vp, C.c_int, C.c_longlong, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.realb_grouped_moe_ffn_gate_up.argtypes = [vp, C.c_int, vp, C.c_int, C.c_longlong, vp, vp, vp, vp, vp, vp, vp]
+    lib.realb_grouped_moe_ffn_down.argtypes = [vp, C.c_int, vp, C.c_int, C.c_longlong, vp, vp, vp, vp, vp, vp]
     lib.realb_combine.argtypes = [vp, vp, vp, vp, C.c_int, vp, vp]
     lib.realb_layer_forward.argtypes = [vp, C.POINTER(LayerIO), vp]
     lib.realb_rank_forward.argtypes = [vp, C.POINTER(LayerIO), C.c_int, vp]
@@ -225,6 +227,16 @@ class Context:
             args = (_p(b.x_perm), None, _p(w13), None, _p(w2), None)
         _check(self.lib.realb_grouped_moe_ffn(self._h, prec, _p(b.expert_offsets), b.n_local, b.max_rows, *args,
                                               _p(b.h_mid), _p(b.h_s), _p(b.y_rows), _stream(stream)))
+
+    def grouped_moe_ffn_gate_up(self, prec: int, w13, b: LayerBuffers, stream=None):
+        args = (_p(b.x_q), _p(b.x_s), _p(b.w13_q), _p(b.w13_s)) if prec == FP4 else (_p(b.x_perm), None, _p(w13), None)
+        _check(self.lib.realb_grouped_moe_ffn_gate_up(self._h, prec, _p(b.expert_offsets), b.n_local, b.max_rows, *args,
+                                                      _p(b.h_mid), _p(b.h_s), _stream(stream)))
+
+    def grouped_moe_ffn_down(self, prec: int, w2, b: LayerBuffers, stream=None):
+        args = (_p(b.w2_q), _p(b.w2_s)) if prec == FP4 else (_p(w2), None)
+        _check(self.lib.realb_grouped_moe_ffn_down(self._h, prec, _p(b.expert_offsets), b.n_local, b.max_rows,
+                                                   _p(b.h_mid), _p(b.h_s), *args, _p(b.y_rows), _stream(stream)))
 
     def combine(self, b: LayerBuffers, stream=None):
         _check(self.lib.realb_combine(self._h, _p(b.y_rows), _p(b.assign_to_row), _p(b.topk_w), b.T, _p(b.out), _stream(stream)))

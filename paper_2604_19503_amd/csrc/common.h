@@ -9,7 +9,7 @@
 namespace realb {
 
 constexpr int kWave = 64;
-constexpr int kPermChunk = 1024;   // assignments ranked by one wave in permute
+constexpr int kPermChunk = 256;    // assignments ranked by one wave in permute
 
 struct Ctx {
     realb_config cfg;

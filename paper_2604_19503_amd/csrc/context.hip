@@ -29,6 +29,7 @@ static int check_shape(const realb_config* c) {
     REALB_REQUIRE(c->E / c->D <= 64, REALB_ESHAPE, "n_local=%d exceeds 64", c->E / c->D);
     REALB_REQUIRE(c->D <= 64, REALB_ESHAPE, "D=%d exceeds 64", c->D);
     REALB_REQUIRE(c->H % 128 == 0 && c->I % 128 == 0, REALB_ESHAPE, "H=%d and I=%d must be multiples of 128", c->H, c->I);
+    REALB_REQUIRE(c->H <= 8192, REALB_ESHAPE, "H=%d exceeds 8192", c->H);
     REALB_REQUIRE((long long)c->T_max * c->k < (1ll << 31), REALB_ESHAPE, "T_max*k overflows int32");
     return REALB_OK;
 }

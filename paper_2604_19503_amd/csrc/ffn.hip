@@ -30,9 +30,15 @@ typedef __attribute__((ext_vector_type(8))) __bf16 v8bf_t;
 constexpr int BM = 256;              // activation rows per block
 constexpr int BNW = 128;             // weight rows per block
 constexpr int KSTEP_BYTES = 64;      // bytes of each operand row per K-step
-constexpr int SLICE_A = BM * 32;     // LDS bytes of one K-slice of the A tile
-constexpr int SLICE_B = BNW * 32;
-constexpr int STAGE_BYTES = 2 * SLICE_A + 2 * SLICE_B;   // 24576
+// LDS stage layout: a 64-byte row segment is split into its four 16-byte parts p = 2*slice + half
+// (the unit one lane feeds to one MFMA), and each part has its own sub-array indexed by row:
+// [p][row][16 B].  A wave's fragment read (32 consecutive rows, fixed p) is then 512 contiguous
+// bytes, and the 32-byte pad between sub-arrays spreads the four parts a lane quad writes over
+// different banks.
+constexpr int SUB_A = BM * 16 + 32;
+constexpr int SUB_B = BNW * 16 + 32;
+constexpr int REGION_A = 4 * SUB_A;
+constexpr int STAGE_BYTES = 4 * SUB_A + 4 * SUB_B;       // 24832
 constexpr int HST = 128 + 16;        // LDS row stride of the staged h tile (64 bf16 + pad)
 constexpr int YST = 256 + 16;        // LDS row stride of the staged y tile (128 bf16 + pad)
 
@@ -112,7 +118,7 @@ __global__ void __launch_bounds__(256, 2) ffn_gemm_kernel(const GemmParams p) {
         const int r = (tid >> 2) + 64 * j;
         const int gr = min(row0 + r, seg_hi - 1);
         a_src[j] = p.A + (size_t)gr * rowbytes + part * 16;
-        a_dst[j] = (part >> 1) * SLICE_A + r * 32 + (part & 1) * 16;
+        a_dst[j] = part * SUB_A + r * 16;
     }
     const uint8_t* b_src[2];
     int b_dst[2];
@@ -121,7 +127,7 @@ __global__ void __launch_bounds__(256, 2) ffn_gemm_kernel(const GemmParams p) {
         const int br = (tid >> 2) + 64 * j;
         const int wrow = GATEUP ? (j == 0 ? n0 + br : I_up + n0 + (br - 64)) : n0 + br;
         b_src[j] = p.W + ((size_t)e * p.w_rows + wrow) * rowbytes + part * 16;
-        b_dst[j] = 2 * SLICE_A + (part >> 1) * SLICE_B + br * 32 + (part & 1) * 16;
+        b_dst[j] = REGION_A + part * SUB_B + br * 16;
     }
 
     // ---- FP4: all scale bytes of the tile's rows, one dword per row per K-step
@@ -152,6 +158,9 @@ __global__ void __launch_bounds__(256, 2) ffn_gemm_kernel(const GemmParams p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    // ---- software pipeline: LDS holds K-step ks (double buffered), registers hold K-step ks+1,
+    //      whose global loads were issued a whole iteration earlier; the scheduling barriers keep
+    //      the LDS refill and the next loads BEHIND the iteration's MFMAs.
     u32x4_t ga[4], gb[2];
 #pragma unroll
     for (int j = 0; j < 4; ++j) ga[j] = *reinterpret_cast<const u32x4_t*>(a_src[j]);
@@ -161,14 +170,20 @@ __global__ void __launch_bounds__(256, 2) ffn_gemm_kernel(const GemmParams p) {
     for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4_t*>(smem + a_dst[j]) = ga[j];
 #pragma unroll
     for (int j = 0; j < 2; ++j) *reinterpret_cast<u32x4_t*>(smem + b_dst[j]) = gb[j];
+    if (nks > 1) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) ga[j] = *reinterpret_cast<const u32x4_t*>(a_src[j] + KSTEP_BYTES);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) gb[j] = *reinterpret_cast<const u32x4_t*>(b_src[j] + KSTEP_BYTES);
+    }
     __syncthreads();
 
     // fragment addresses inside a stage
-    const int a_frag = (wm * 128 + li) * 32 + half * 16;                       // + mt*1024 + slice*SLICE_A
+    const int a_frag = half * SUB_A + (wm * 128 + li) * 16;                    // + mt*512 + slice*2*SUB_A
     const int b_row0 = GATEUP ? wn * 32 : wn * 64;                             // tile 0 rows
     const int b_row1 = GATEUP ? 64 + wn * 32 : wn * 64 + 32;                   // tile 1 rows
-    const int b_frag0 = 2 * SLICE_A + (b_row0 + li) * 32 + half * 16;          // + slice*SLICE_B
-    const int b_frag1 = 2 * SLICE_A + (b_row1 + li) * 32 + half * 16;
+    const int b_frag0 = REGION_A + half * SUB_B + (b_row0 + li) * 16;          // + slice*2*SUB_B
+    const int b_frag1 = REGION_A + half * SUB_B + (b_row1 + li) * 16;
     const int sa_idx = (wm * 128 + li) * spd;                                  // + mt*32*spd + ks
     const int sb_idx0 = (BM + b_row0 + li) * spd;
     const int sb_idx1 = (BM + b_row1 + li) * spd;
@@ -176,13 +191,6 @@ __global__ void __launch_bounds__(256, 2) ffn_gemm_kernel(const GemmParams p) {
 
     for (int ks = 0; ks < nks; ++ks) {
         const uint8_t* st = smem + (ks & 1) * STAGE_BYTES;
-        const bool more = ks + 1 < nks;
-        if (more) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) ga[j] = *reinterpret_cast<const u32x4_t*>(a_src[j] + (size_t)(ks + 1) * KSTEP_BYTES);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) gb[j] = *reinterpret_cast<const u32x4_t*>(b_src[j] + (size_t)(ks + 1) * KSTEP_BYTES);
-        }
         int sa[4] = {0, 0, 0, 0}, sb[2] = {0, 0};
         if constexpr (FP4) {
 #pragma unroll
@@ -190,36 +198,39 @@ __global__ void __launch_bounds__(256, 2) ffn_gemm_kernel(const GemmParams p) {
             sb[0] = (int)(sc[sb_idx0 + ks] >> sshift);
             sb[1] = (int)(sc[sb_idx1 + ks] >> sshift);
         }
-        {   // K-slice 0
-            u32x4_t fa[4], fb[2];
+        u32x4_t fa0[4], fb0[2], fa1[4], fb1[2];
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) fa[mt] = *reinterpret_cast<const u32x4_t*>(st + a_frag + mt * 1024);
-            fb[0] = *reinterpret_cast<const u32x4_t*>(st + b_frag0);
-            fb[1] = *reinterpret_cast<const u32x4_t*>(st + b_frag1);
+        for (int mt = 0; mt < 4; ++mt) fa0[mt] = *reinterpret_cast<const u32x4_t*>(st + a_frag + mt * 512);
+        fb0[0] = *reinterpret_cast<const u32x4_t*>(st + b_frag0);
+        fb0[1] = *reinterpret_cast<const u32x4_t*>(st + b_frag1);
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) {
-                mma<FP4, 0>(acc[mt][0], fa[mt], fb[0], sa[mt], sb[0]);
-                mma<FP4, 0>(acc[mt][1], fa[mt], fb[1], sa[mt], sb[1]);
-            }
+        for (int mt = 0; mt < 4; ++mt) fa1[mt] = *reinterpret_cast<const u32x4_t*>(st + 2 * SUB_A + a_frag + mt * 512);
+        fb1[0] = *reinterpret_cast<const u32x4_t*>(st + 2 * SUB_B + b_frag0);
+        fb1[1] = *reinterpret_cast<const u32x4_t*>(st + 2 * SUB_B + b_frag1);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {                     // K-slice 0: scale bytes 0/1 of the K-step's dword
+            mma<FP4, 0>(acc[mt][0], fa0[mt], fb0[0], sa[mt], sb[0]);
+            mma<FP4, 0>(acc[mt][1], fa0[mt], fb0[1], sa[mt], sb[1]);
         }
-        {   // K-slice 1 (scale bytes 2 and 3 of the K-step's dword)
-            u32x4_t fa[4], fb[2];
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) fa[mt] = *reinterpret_cast<const u32x4_t*>(st + SLICE_A + a_frag + mt * 1024);
-            fb[0] = *reinterpret_cast<const u32x4_t*>(st + SLICE_B + b_frag0);
-            fb[1] = *reinterpret_cast<const u32x4_t*>(st + SLICE_B + b_frag1);
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt) {
-                mma<FP4, 2>(acc[mt][0], fa[mt], fb[0], sa[mt], sb[0]);
-                mma<FP4, 2>(acc[mt][1], fa[mt], fb[1], sa[mt], sb[1]);
-            }
+        for (int mt = 0; mt < 4; ++mt) {                     // K-slice 1: scale bytes 2/3
+            mma<FP4, 2>(acc[mt][0], fa1[mt], fb1[0], sa[mt], sb[0]);
+            mma<FP4, 2>(acc[mt][1], fa1[mt], fb1[1], sa[mt], sb[1]);
         }
-        if (more) {
+        __builtin_amdgcn_sched_barrier(0);
+        if (ks + 1 < nks) {
             uint8_t* nx = smem + ((ks + 1) & 1) * STAGE_BYTES;
 #pragma unroll
             for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4_t*>(nx + a_dst[j]) = ga[j];
 #pragma unroll
             for (int j = 0; j < 2; ++j) *reinterpret_cast<u32x4_t*>(nx + b_dst[j]) = gb[j];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        if (ks + 2 < nks) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) ga[j] = *reinterpret_cast<const u32x4_t*>(a_src[j] + (size_t)(ks + 2) * KSTEP_BYTES);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) gb[j] = *reinterpret_cast<const u32x4_t*>(b_src[j] + (size_t)(ks + 2) * KSTEP_BYTES);
         }
         __syncthreads();
     }
@@ -320,29 +331,50 @@ static int launch_gemm(const GemmParams& p, long long max_rows, hipStream_t s) {
 
 using namespace realb;
 
-extern "C" int realb_grouped_moe_ffn(realb_ctx* ctx, int prec, const int32_t* expert_offsets, int n_local, long long max_rows,
-                                     const void* x, const uint8_t* x_s, const void* w13, const uint8_t* w13_s,
-                                     const void* w2, const uint8_t* w2_s, void* h_mid, uint8_t* h_s, void* y_rows,
-                                     void* stream) {
+static int ffn_stages(realb_ctx* ctx, int prec, int stages, const int32_t* expert_offsets, int n_local, long long max_rows,
+                      const void* x, const uint8_t* x_s, const void* w13, const uint8_t* w13_s, const void* w2,
+                      const uint8_t* w2_s, void* h_mid, uint8_t* h_s, void* y_rows, void* stream) {
     REALB_REQUIRE(ctx && expert_offsets, REALB_EINVAL, "NULL argument");
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     REALB_REQUIRE(prec == REALB_BF16 || prec == REALB_FP4, REALB_EINVAL, "bad precision %d", prec);
     REALB_REQUIRE(n_local >= 0 && n_local <= c->n_local, REALB_ECAP, "n_local=%d exceeds the context's %d", n_local, c->n_local);
     REALB_REQUIRE(max_rows >= 0, REALB_EINVAL, "max_rows < 0");
     if (max_rows == 0 || n_local == 0) return REALB_OK;
-    REALB_REQUIRE(x && w13 && w2 && h_mid && y_rows, REALB_EINVAL, "NULL argument");
-    REALB_REQUIRE(prec == REALB_BF16 || (x_s && w13_s && w2_s && h_s), REALB_EINVAL, "NULL scale tensor on the FP4 path");
+    const bool s1 = stages & 1, s2 = stages & 2;
+    REALB_REQUIRE(h_mid && (!s1 || (x && w13)) && (!s2 || (w2 && y_rows)), REALB_EINVAL, "NULL argument");
+    REALB_REQUIRE(prec == REALB_BF16 || (h_s && (!s1 || (x_s && w13_s)) && (!s2 || w2_s)), REALB_EINVAL,
+                  "NULL scale tensor on the FP4 path");
     const int H = c->cfg.H, I = c->cfg.I;
     hipStream_t s = as_stream(stream);
     GemmParams g1{(const uint8_t*)x, x_s, (const uint8_t*)w13, w13_s, (uint8_t*)h_mid, h_s, expert_offsets, n_local, H, 2 * I, I, I / 64};
     GemmParams g2{(const uint8_t*)h_mid, h_s, (const uint8_t*)w2, w2_s, (uint8_t*)y_rows, nullptr, expert_offsets, n_local, I, H, H, H / 128};
-    int rc;
+    int rc = REALB_OK;
     if (prec == REALB_FP4) {
-        rc = launch_gemm<true, true>(g1, max_rows, s);
-        if (rc == REALB_OK) rc = launch_gemm<true, false>(g2, max_rows, s);
+        if (s1) rc = launch_gemm<true, true>(g1, max_rows, s);
+        if (rc == REALB_OK && s2) rc = launch_gemm<true, false>(g2, max_rows, s);
     } else {
-        rc = launch_gemm<false, true>(g1, max_rows, s);
-        if (rc == REALB_OK) rc = launch_gemm<false, false>(g2, max_rows, s);
+        if (s1) rc = launch_gemm<false, true>(g1, max_rows, s);
+        if (rc == REALB_OK && s2) rc = launch_gemm<false, false>(g2, max_rows, s);
     }
     return rc;
+}
+
+extern "C" int realb_grouped_moe_ffn(realb_ctx* ctx, int prec, const int32_t* expert_offsets, int n_local, long long max_rows,
+                                     const void* x, const uint8_t* x_s, const void* w13, const uint8_t* w13_s,
+                                     const void* w2, const uint8_t* w2_s, void* h_mid, uint8_t* h_s, void* y_rows,
+                                     void* stream) {
+    return ffn_stages(ctx, prec, 3, expert_offsets, n_local, max_rows, x, x_s, w13, w13_s, w2, w2_s, h_mid, h_s, y_rows, stream);
+}
+
+extern "C" int realb_grouped_moe_ffn_gate_up(realb_ctx* ctx, int prec, const int32_t* expert_offsets, int n_local,
+                                             long long max_rows, const void* x, const uint8_t* x_s, const void* w13,
+                                             const uint8_t* w13_s, void* h_mid, uint8_t* h_s, void* stream) {
+    return ffn_stages(ctx, prec, 1, expert_offsets, n_local, max_rows, x, x_s, w13, w13_s, nullptr, nullptr, h_mid, h_s, nullptr, stream);
+}
+
+extern "C" int realb_grouped_moe_ffn_down(realb_ctx* ctx, int prec, const int32_t* expert_offsets, int n_local,
+                                          long long max_rows, const void* h_mid, const uint8_t* h_s, const void* w2,
+                                          const uint8_t* w2_s, void* y_rows, void* stream) {
+    return ffn_stages(ctx, prec, 2, expert_offsets, n_local, max_rows, nullptr, nullptr, nullptr, nullptr, w2, w2_s,
+                      const_cast<void*>(h_mid), const_cast<uint8_t*>(h_s), y_rows, stream);
 }

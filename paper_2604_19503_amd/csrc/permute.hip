@@ -8,23 +8,29 @@
 
 namespace realb {
 
+constexpr int kIters = kPermChunk / 64;   // 64 assignments per wave iteration
+
 // Phase 1: each wave counts, per local expert, the assignments of its chunk of
 // kPermChunk consecutive flat indices a = t*k + j.  Lane e holds expert e's count.
-__global__ void __launch_bounds__(64) perm_count_kernel(const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
-                                                        int32_t* __restrict__ wave_cnt) {
-    const int lane = threadIdx.x;
-    const int chunk = blockIdx.x;
+__global__ void __launch_bounds__(256) perm_count_kernel(const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
+                                                         int n_chunks, int32_t* __restrict__ wave_cnt) {
+    const int lane = threadIdx.x & 63;
+    const int chunk = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (chunk >= n_chunks) return;
     const int begin = chunk * kPermChunk;
-    const int end = min(begin + kPermChunk, A);
+    int le[kIters];
+#pragma unroll
+    for (int i = 0; i < kIters; ++i) {
+        const int a = begin + i * 64 + lane;
+        le[i] = (a < A) ? topk_ids[a] - lo : -1;
+    }
     int cnt = 0;
-    for (int a0 = begin; a0 < end; a0 += 64) {
-        const int a = a0 + lane;
-        const int le = (a < end) ? topk_ids[a] - lo : -1;
+#pragma unroll
+    for (int i = 0; i < kIters; ++i)
         for (int e = 0; e < n_local; ++e) {
-            const unsigned long long m = __ballot(le == e);
+            const unsigned long long m = __ballot(le[i] == e);
             if (lane == e) cnt += __popcll(m);
         }
-    }
     if (lane < n_local) wave_cnt[chunk * n_local + lane] = cnt;
 }
 
@@ -67,71 +73,97 @@ __global__ void __launch_bounds__(1024) perm_scan_kernel(int32_t* __restrict__ w
 
 // Phase 3: each wave walks its chunk again and gives every local assignment its
 // row: expert_offsets[e] + (rank of the chunk's first) + (rank inside the chunk).
-__global__ void __launch_bounds__(64) perm_rank_kernel(const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
-                                                       const int32_t* __restrict__ wave_cnt,
-                                                       const int32_t* __restrict__ expert_offsets,
-                                                       int32_t* __restrict__ row_to_assign, int32_t* __restrict__ assign_to_row) {
-    const int lane = threadIdx.x;
-    const int chunk = blockIdx.x;
+__global__ void __launch_bounds__(256) perm_rank_kernel(const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
+                                                        int n_chunks, const int32_t* __restrict__ wave_cnt,
+                                                        const int32_t* __restrict__ expert_offsets,
+                                                        int32_t* __restrict__ row_to_assign, int32_t* __restrict__ assign_to_row) {
+    const int lane = threadIdx.x & 63;
+    const int chunk = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (chunk >= n_chunks) return;
     const int begin = chunk * kPermChunk;
-    const int end = min(begin + kPermChunk, A);
+    int le[kIters];
+#pragma unroll
+    for (int i = 0; i < kIters; ++i) {
+        const int a = begin + i * 64 + lane;
+        le[i] = (a < A) ? topk_ids[a] - lo : -1;
+    }
     int running = (lane < n_local) ? expert_offsets[lane] + wave_cnt[chunk * n_local + lane] : 0;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
-    for (int a0 = begin; a0 < end; a0 += 64) {
-        const int a = a0 + lane;
-        const int le = (a < end) ? topk_ids[a] - lo : -1;
+#pragma unroll
+    for (int i = 0; i < kIters; ++i) {
+        const int a = begin + i * 64 + lane;
         int row = -1;
         for (int e = 0; e < n_local; ++e) {
-            const unsigned long long m = __ballot(le == e);
-            const int base = __shfl(running, e);
-            if (le == e) row = base + __popcll(m & lt_mask);
+            const unsigned long long m = __ballot(le[i] == e);
+            const int base = __builtin_amdgcn_readlane(running, e);
+            if (le[i] == e) row = base + __popcll(m & lt_mask);
             if (lane == e) running += __popcll(m);
         }
-        if (a < end) {
+        if (a < A) {
             assign_to_row[a] = row;
             if (row >= 0) row_to_assign[row] = a;
         }
     }
 }
 
-// Phase 4: one wave per row, grid-strided; R is read from expert_offsets[n_local].
+// Phase 4: one wave per TOKEN, grid-strided: a token routed to several local experts
+// is read (and, on the FP4 path, encoded) once and written to each of its rows.
 // H/8 chunks of 16 B per row; FP4: quads of lanes share one 32-element block.
-template <bool FP4>
-__global__ void __launch_bounds__(256) perm_gather_kernel(const u32x4_t* __restrict__ x, const int32_t* __restrict__ row_to_assign,
-                                                          const int32_t* __restrict__ expert_offsets, int n_local, int k,
-                                                          int H, u32x4_t* __restrict__ x_perm, uint32_t* __restrict__ x_q,
-                                                          uint8_t* __restrict__ x_s) {
-    const int R = expert_offsets[n_local];
+template <bool FP4, int CPL>   // CPL = 16-byte chunks per lane = H / 512 rounded up
+__global__ void __launch_bounds__(256) perm_gather_kernel(const u32x4_t* __restrict__ x, const int32_t* __restrict__ assign_to_row,
+                                                          int T, int k, int H, u32x4_t* __restrict__ x_perm,
+                                                          uint32_t* __restrict__ x_q, uint8_t* __restrict__ x_s) {
     const int lane = threadIdx.x & 63;
     const int chunks = H >> 3;                             // 16-B chunks per row, multiple of 16
     const int wave_global = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
     const int n_waves = gridDim.x * (blockDim.x >> 6);
-    for (int r = wave_global; r < R; r += n_waves) {
-        const int t = row_to_assign[r] / k;
+    for (int t = wave_global; t < T; t += n_waves) {
+        const int my_row = lane < k ? assign_to_row[(size_t)t * k + lane] : -1;
+        if (__ballot(my_row >= 0) == 0ull) continue;       // no local expert for this token
         const u32x4_t* src = x + (size_t)t * chunks;
-        for (int c0 = 0; c0 < chunks; c0 += 256) {
-            u32x4_t v[4];
+        u32x4_t v[CPL];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int c = c0 + u * 64 + lane;
-                v[u] = c < chunks ? src[c] : u32x4_t{0, 0, 0, 0};
-            }
+        for (int u = 0; u < CPL; ++u) {
+            const int c = u * 64 + lane;
+            v[u] = c < chunks ? src[c] : u32x4_t{0, 0, 0, 0};
+        }
+        uint32_t codes[CPL], byte[CPL];
+        if (FP4) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int c = c0 + u * 64 + lane;
-                if (FP4) {
-                    uint32_t byte;
-                    const uint32_t codes = encode_block_quad(v[u], &byte);
-                    if (c < chunks) {
-                        x_q[(size_t)r * chunks + c] = codes;
-                        if ((lane & 3) == 0) x_s[(size_t)r * (chunks >> 2) + (c >> 2)] = (uint8_t)byte;
+            for (int u = 0; u < CPL; ++u) codes[u] = encode_block_quad(v[u], &byte[u]);
+        }
+        for (int j = 0; j < k; ++j) {
+            const int r = __builtin_amdgcn_readlane(my_row, j);
+            if (r < 0) continue;
+#pragma unroll
+            for (int u = 0; u < CPL; ++u) {
+                const int c = u * 64 + lane;
+                if (c < chunks) {
+                    if (FP4) {
+                        x_q[(size_t)r * chunks + c] = codes[u];
+                        if ((lane & 3) == 0) x_s[(size_t)r * (chunks >> 2) + (c >> 2)] = (uint8_t)byte[u];
+                    } else {
+                        x_perm[(size_t)r * chunks + c] = v[u];
                     }
-                } else if (c < chunks) {
-                    x_perm[(size_t)r * chunks + c] = v[u];
                 }
             }
         }
     }
+}
+
+template <bool FP4>
+static void launch_gather(int blocks, hipStream_t s, const void* x, const int32_t* a2r, int T, int k, int H, void* x_perm,
+                          uint8_t* x_q, uint8_t* x_s) {
+    const int cpl = (H / 8 + 63) / 64;
+#define REALB_GATHER(CPL)                                                                                              \
+    hipLaunchKernelGGL((perm_gather_kernel<FP4, CPL>), dim3(blocks), dim3(256), 0, s, (const u32x4_t*)x, a2r, T, k, H, \
+                       (u32x4_t*)x_perm, (uint32_t*)x_q, x_s)
+    if (cpl <= 1) REALB_GATHER(1);
+    else if (cpl <= 2) REALB_GATHER(2);
+    else if (cpl <= 4) REALB_GATHER(4);
+    else if (cpl <= 8) REALB_GATHER(8);
+    else REALB_GATHER(16);
+#undef REALB_GATHER
 }
 
 }  // namespace realb
@@ -155,19 +187,16 @@ extern "C" int realb_permute(realb_ctx* ctx, const void* x, const int32_t* topk_
     hipStream_t s = as_stream(stream);
     const int n_chunks = ceil_div(A, kPermChunk);
     const int lo = rank * n_local;
+    const int chunk_blocks = ceil_div(n_chunks, 4);
     if (n_chunks > 0)
-        hipLaunchKernelGGL(perm_count_kernel, dim3(n_chunks), dim3(64), 0, s, topk_ids, (int)A, lo, n_local, c->wave_cnt);
+        hipLaunchKernelGGL(perm_count_kernel, dim3(chunk_blocks), dim3(256), 0, s, topk_ids, (int)A, lo, n_local, n_chunks, c->wave_cnt);
     hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, s, c->wave_cnt, n_chunks, n_local, expert_offsets);
     if (n_chunks > 0) {
-        hipLaunchKernelGGL(perm_rank_kernel, dim3(n_chunks), dim3(64), 0, s, topk_ids, (int)A, lo, n_local, c->wave_cnt,
-                           expert_offsets, row_to_assign, assign_to_row);
-        const int blocks = (int)(worst < 4 ? 1 : (worst / 4 < 256 * 16 ? worst / 4 : 256 * 16));
-        if (prec == REALB_FP4)
-            hipLaunchKernelGGL(perm_gather_kernel<true>, dim3(blocks), dim3(256), 0, s, (const u32x4_t*)x, row_to_assign,
-                               expert_offsets, n_local, k, H, (u32x4_t*)nullptr, (uint32_t*)x_q, x_s);
-        else
-            hipLaunchKernelGGL(perm_gather_kernel<false>, dim3(blocks), dim3(256), 0, s, (const u32x4_t*)x, row_to_assign,
-                               expert_offsets, n_local, k, H, (u32x4_t*)x_perm, (uint32_t*)nullptr, (uint8_t*)nullptr);
+        hipLaunchKernelGGL(perm_rank_kernel, dim3(chunk_blocks), dim3(256), 0, s, topk_ids, (int)A, lo, n_local, n_chunks,
+                           c->wave_cnt, expert_offsets, row_to_assign, assign_to_row);
+        const int blocks = T < 4 ? 1 : (T / 4 < 256 * 16 ? T / 4 : 256 * 16);
+        if (prec == REALB_FP4) launch_gather<true>(blocks, s, x, assign_to_row, T, k, H, nullptr, x_q, x_s);
+        else launch_gather<false>(blocks, s, x, assign_to_row, T, k, H, x_perm, nullptr, nullptr);
     }
     REALB_HIP(hipGetLastError());
     return REALB_OK;

@@ -3,6 +3,7 @@ CPU oracle on the same seeded inputs.  Integer / byte / index results must be
 bit-exact; GEMM and combine outputs are compared by relative Frobenius error with
 the tolerances of the benchmark spec: 2e-3 on the FP4 path (against the
 oracle run on the same dequantised operands) and 1e-2 on the BF16 path."""
+import os
 import sys
 
 import numpy as np
@@ -23,6 +24,10 @@ MAX_FLIP_FRACTION = 1e-3
 def _say(msg):
     print(f"[gpu-parity] {msg}", flush=True)
     sys.stdout.flush()
+    out_dir = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(out_dir):
+        with open(os.path.join(out_dir, "parity_metrics.log"), "a") as f:
+            f.write(msg + "\n")
 
 
 @pytest.fixture(scope="module")
