@@ -37,6 +37,7 @@ def parse():
     ap.add_argument("--precision", default="fp4", choices=["fp4", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true")
+    ap.add_argument("--gemm-tile", type=int, default=0, choices=[0, 2, 8], help="grouped-GEMM block tile selector (0 = automatic)")
     ap.add_argument("--detail", default=None, help="write the per-kernel breakdown (JSON) to this path")
     return ap.parse_args()
 
@@ -110,6 +111,9 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(1)
     torch.cuda.set_device(0)
+    if args.gemm_tile:
+        from paper_2604_19503_amd.binding import set_gemm_tile
+        set_gemm_tile(args.gemm_tile)
     cfg = W.CONFIGS[args.workload]
     fp4 = args.precision == "fp4"
     force = R.FP4 if fp4 else R.BF16

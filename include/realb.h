@@ -161,6 +161,12 @@ int realb_grouped_moe_ffn_down(realb_ctx* ctx, int prec, const int32_t* expert_o
                                long long max_rows, const void* h_mid, const uint8_t* h_s,
                                const void* w2, const uint8_t* w2_s, void* y_rows, void* stream);
 
+/* Tuning hook for the grouped GEMMs' block tile: 0 = automatic (default), 2 = 256x128
+ * tiles with two blocks per CU, 8 = 256x256 tiles with 8 waves and one block per CU (used
+ * only where the output width is a multiple of the tile).  Process-wide; outputs are
+ * bit-identical for every choice (the accumulation order along K does not change). */
+int realb_set_gemm_tile(int wn);
+
 /* Unpermute + weighted combine (local part of the result combination):
  * out[t] = sum over j with assign_to_row[t*k+j] >= 0 of topk_w[t,j] * y_rows[row],
  * FP32 accumulate in order of j, rounded once to BF16; tokens with no local

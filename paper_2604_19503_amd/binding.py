@@ -15,7 +15,7 @@ EXPORTS = [
     "realb_default_config", "realb_create", "realb_destroy", "realb_last_error", "realb_get_M", "realb_set_M",
     "realb_route_stats", "realb_select_precision", "realb_select_precision_host", "realb_quantize_experts_fp4",
     "realb_quantize_rows_fp4", "realb_permute", "realb_grouped_moe_ffn", "realb_grouped_moe_ffn_gate_up",
-    "realb_grouped_moe_ffn_down", "realb_combine", "realb_layer_forward", "realb_rank_forward",
+    "realb_grouped_moe_ffn_down", "realb_set_gemm_tile", "realb_combine", "realb_layer_forward", "realb_rank_forward",
 ]
 
 
@@ -109,6 +109,10 @@ def bf16_from_bits(bits: np.ndarray, device="cuda") -> torch.Tensor:
 
 def bits_from_bf16(t: torch.Tensor) -> np.ndarray:
     return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def set_gemm_tile(wn: int):
+    _check(load_library().realb_set_gemm_tile(int(wn)))
 
 
 def default_config(T_max, E, k, D, H, I) -> Config:

@@ -15,6 +15,7 @@ struct Ctx {
     realb_config cfg;
     int n_local;
     int device;
+    int num_cus;
     double M;
     // device workspace
     int32_t* wave_cnt;     // [n_chunks_max, n_local]  per-chunk local-expert counts, then exclusive bases

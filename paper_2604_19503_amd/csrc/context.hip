@@ -96,6 +96,7 @@ int realb_create(const realb_config* cfg, realb_ctx** out) {
     c->M = cfg->M_init;
     c->wave_cnt = nullptr; c->stats_host = nullptr; c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr;
     hipError_t e = hipGetDevice(&c->device);
+    if (e == hipSuccess) e = hipDeviceGetAttribute(&c->num_cus, hipDeviceAttributeMultiprocessorCount, c->device);
     long long A_max = (long long)cfg->T_max * cfg->k;
     c->n_chunks_max = ceil_div(A_max, kPermChunk) + 1;
     if (e == hipSuccess) e = hipMalloc((void**)&c->wave_cnt, (size_t)c->n_chunks_max * c->n_local * sizeof(int32_t));

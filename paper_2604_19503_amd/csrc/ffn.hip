@@ -9,13 +9,18 @@
 // one row (8 BF16 values, or the 32 FP4 values of exactly one MX block, whose
 // E8M0 scale is therefore one byte per lane).
 //
-// Block tile: 256 activation rows x 128 weight rows, 4 waves as 2x2, each wave
-// 128 x 64 = 4 x 2 MFMA tiles of 32x32 (128 accumulator registers).
-//   gate/up : the 128 weight rows are 64 gate rows n0.. and the 64 matching up
-//             rows I+n0.., arranged so a wave holds gate and up of the same 32
-//             columns -> SwiGLU is element-wise in registers; h is rounded to
-//             BF16, staged in LDS, then stored as BF16 or re-encoded to MXFP4.
-//   down    : 128 output columns, staged in LDS, stored as BF16 rows.
+// The MFMA runs "transposed": the weight rows are its A operand and the
+// activation rows its B operand, so a lane ends up with one activation row and
+// 16 weight rows.  The weight rows of a 32-row tile are stored in LDS in a
+// permuted order chosen so that those 16 are CONSECUTIVE output columns
+// (columns 16*half .. 16*half+15 of the tile, half = lane/32).  The epilogues
+// therefore need no LDS and no barrier:
+//   gate/up : a wave holds the gate and the up tile of the same 32 columns, so
+//             SwiGLU is element-wise in registers; h is rounded to BF16 and a
+//             lane stores 32 contiguous bytes, or -- FP4 path -- shares the
+//             block maximum with lane^32 (the other 16 columns of the MX block),
+//             encodes its 16 values and stores 8 contiguous code bytes.
+//   down    : a lane stores 32 contiguous bytes of its output row per tile.
 // Tiles never straddle experts; row tails are clamped on load and masked on
 // store.  expert_offsets is read on the device, so no host round trip.
 #include "common.h"
@@ -26,21 +31,31 @@ namespace realb {
 typedef __attribute__((ext_vector_type(8))) int v8i_t;
 typedef __attribute__((ext_vector_type(16))) float v16f_t;
 typedef __attribute__((ext_vector_type(8))) __bf16 v8bf_t;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2_t;
 
 constexpr int BM = 256;              // activation rows per block
-constexpr int BNW = 128;             // weight rows per block
 constexpr int KSTEP_BYTES = 64;      // bytes of each operand row per K-step
+
+// Tile geometry: the block has 2 x WGN waves (rows x columns); a wave owns 128 activation rows
+// x WN*32 weight rows, i.e. 4 x WN MFMA tiles of 32x32.
+//
 // LDS stage layout: a 64-byte row segment is split into its four 16-byte parts p = 2*slice + half
 // (the unit one lane feeds to one MFMA), and each part has its own sub-array indexed by row:
 // [p][row][16 B].  A wave's fragment read (32 consecutive rows, fixed p) is then 512 contiguous
 // bytes, and the 32-byte pad between sub-arrays spreads the four parts a lane quad writes over
 // different banks.
-constexpr int SUB_A = BM * 16 + 32;
-constexpr int SUB_B = BNW * 16 + 32;
-constexpr int REGION_A = 4 * SUB_A;
-constexpr int STAGE_BYTES = 4 * SUB_A + 4 * SUB_B;       // 24832
-constexpr int HST = 128 + 16;        // LDS row stride of the staged h tile (64 bf16 + pad)
-constexpr int YST = 256 + 16;        // LDS row stride of the staged y tile (128 bf16 + pad)
+template <int WN, int WGN>
+struct Geo {
+    static constexpr int NT = 128 * WGN;                // threads per block
+    static constexpr int BNW = 32 * WN * WGN;           // weight rows per block
+    static constexpr int GC = BNW / 2;                  // gate/up: h columns per block
+    static constexpr int SUB_A = BM * 16 + 32;
+    static constexpr int SUB_B = BNW * 16 + 32;
+    static constexpr int REGION_A = 4 * SUB_A;
+    static constexpr int STAGE = 4 * SUB_A + 4 * SUB_B;
+    static constexpr int JA = BM * 4 / NT;              // 16-byte global loads per thread per K-step, activations
+    static constexpr int JB = BNW * 4 / NT;             //                                           , weights
+};
 
 struct GemmParams {
     const uint8_t* A;        // activations: bf16 [rows,K] or fp4 codes [rows,K/2]
@@ -54,45 +69,53 @@ struct GemmParams {
     int K;                   // contraction length in elements
     int w_rows;              // weight rows per expert (2I or H)
     int n_out;               // output columns (I or H)
-    int n_tiles_n;           // column tiles (I/64 or H/128)
+    int n_tiles_n;           // column tiles (I/GC or H/BNW)
 };
 
 __host__ __device__ __forceinline__ size_t lds_scale_stride_dwords(int K) { return (size_t)((K >> 7) | 1); }
 
+// acc += W_tile (A operand, 32 weight rows) x X_tile^T (B operand, 32 activation rows)
 template <bool FP4, int OPSEL>
-__device__ __forceinline__ void mma(v16f_t& acc, const u32x4_t& a, const u32x4_t& b, int sa, int sb) {
+__device__ __forceinline__ void mma(v16f_t& acc, const u32x4_t& w, const u32x4_t& x, int sw, int sx) {
     if constexpr (FP4) {
-        v8i_t a8 = {(int)a.x, (int)a.y, (int)a.z, (int)a.w, 0, 0, 0, 0};
-        v8i_t b8 = {(int)b.x, (int)b.y, (int)b.z, (int)b.w, 0, 0, 0, 0};
-        acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, acc, 4, 4, OPSEL, sa, OPSEL, sb);
+        v8i_t a8 = {(int)w.x, (int)w.y, (int)w.z, (int)w.w, 0, 0, 0, 0};
+        v8i_t b8 = {(int)x.x, (int)x.y, (int)x.z, (int)x.w, 0, 0, 0, 0};
+        acc = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8, b8, acc, 4, 4, OPSEL, sw, OPSEL, sx);
     } else {
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf_t, a), __builtin_bit_cast(v8bf_t, b), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf_t, w), __builtin_bit_cast(v8bf_t, x), acc, 0, 0, 0);
     }
 }
 
-__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
-    __bf16 b = (__bf16)f;
-    return __builtin_bit_cast(uint16_t, b);
+// two floats -> two BF16 (nearest even) in one dword, first in the low half
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    typedef __attribute__((ext_vector_type(2))) __bf16 bf2;
+    bf2 v = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(uint32_t, v);
 }
 
-template <bool FP4, bool GATEUP>
-__global__ void __launch_bounds__(256, 2) ffn_gemm_kernel(const GemmParams p) {
-    extern __shared__ __align__(16) uint8_t smem[];
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    const int li = lane & 31, half = lane >> 5;
+// Weight row (within the expert) of row `br` of the block's weight tile.
+template <bool GATEUP, int GC>
+__device__ __forceinline__ int w_tile_row(int br, int n0, int I_up) {
+    if constexpr (GATEUP) return br < GC ? n0 + br : I_up + n0 + (br - GC);
+    else return n0 + br;
+}
 
-    // ---- which tile: blocks b, b+8, b+16, .. share an XCD (and its L2), so each XCD takes a
-    //      contiguous range of tiles = consecutive row tiles over all column tiles.
-    int total_m = 0;
-    for (int e = 0; e < p.n_local; ++e) total_m += (p.offs[e + 1] - p.offs[e] + BM - 1) / BM;
-    const int total = total_m * p.n_tiles_n;
-    const int per_xcd = (total + 7) >> 3;
-    const int slot = blockIdx.x >> 3;
-    const int tile = (blockIdx.x & 7) * per_xcd + slot;
-    if (slot >= per_xcd || tile >= total) return;
+// LDS slot of weight-tile row br: inside each group of 32 rows, row 16h + 4g + q sits in slot
+// 8g + 4h + q.  MFMA output row i = 8g + 4h + q lands in lane half h, register 4g + q, so the
+// lane's 16 registers are weight rows 16h .. 16h+15 of the tile, in order.
+__device__ __forceinline__ int w_slot(int br) { return (br & ~31) | (((br >> 2) & 3) << 3) | (((br >> 4) & 1) << 2) | (br & 3); }
+// inverse: the weight-tile row that lane li (slot li) feeds to the MFMA
+__device__ __forceinline__ int w_row_of_lane(int li) { return (((li >> 2) & 1) << 4) | ((li >> 3) << 2) | (li & 3); }
+
+struct TileInfo {
+    int e;        // local expert
+    int row0;     // first activation row of the tile
+    int seg_hi;   // end of the expert's row segment
+    int n0;       // first output column of the tile
+};
+
+// Tile index -> (expert, row tile, column tile); column tiles are the fast index.
+__device__ __forceinline__ TileInfo decode_tile(const GemmParams& p, int tile, int cols_per_tile) {
     int mi = tile / p.n_tiles_n;
     const int nt = tile - mi * p.n_tiles_n;
     int e = 0, seg_lo = 0, seg_hi = 0;
@@ -103,233 +126,304 @@ __global__ void __launch_bounds__(256, 2) ffn_gemm_kernel(const GemmParams p) {
         if (mi < te) break;
         mi -= te;
     }
-    const int row0 = seg_lo + mi * BM;
-    const int n0 = nt * (GATEUP ? 64 : 128);
+    return TileInfo{e, seg_lo + mi * BM, seg_hi, nt * cols_per_tile};
+}
+
+// Blocks b, b+8, b+16, .. share an XCD (and its L2), so each XCD takes a contiguous range of tiles
+// (consecutive row tiles over all column tiles).  BF16: persistent blocks, one per residency slot,
+// walk their XCD's range with a stride, and while a tile's epilogue runs the first K-step of the
+// block's next tile is already in flight.  FP4: one tile per block (grid = worst-case tile count).
+template <bool FP4, bool GATEUP, int WN, int WGN, int MINB>
+__global__ void __launch_bounds__(128 * WGN, MINB) ffn_gemm_kernel(const GemmParams p) {
+    using G = Geo<WN, WGN>;
+    constexpr int NT = G::NT;
+    constexpr int COLS = GATEUP ? G::GC : G::BNW;
+    constexpr bool PERSIST = !FP4;    // the FP4 body has no registers to spare for a tile carried across the epilogue
+    constexpr int SBATCH = FP4 ? (BM + G::BNW) * 16 / NT : 1;         // scale dwords per thread (covers K <= 2048 at once)
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+    const int li = lane & 31, half = lane >> 5;
+
+    int total_m = 0;
+    for (int e = 0; e < p.n_local; ++e) total_m += (p.offs[e + 1] - p.offs[e] + BM - 1) / BM;
+    const int total = total_m * p.n_tiles_n;
+    const int per_xcd = (total + 7) >> 3;
+    const int nslots = gridDim.x >> 3;
+    const int tile_hi = min(total, ((int)(blockIdx.x & 7) + 1) * per_xcd);
+    int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tile >= tile_hi) return;
+
     const int I_up = p.w_rows >> 1;                       // gate/up: offset of the up rows
     const size_t rowbytes = FP4 ? (size_t)(p.K >> 1) : (size_t)p.K * 2;
     const int nks = (int)(rowbytes / KSTEP_BYTES);
-
-    // ---- global -> LDS copy assignment: 16-byte chunks, 4 per 64-byte row segment
-    const int part = tid & 3;
-    const uint8_t* a_src[4];
-    int a_dst[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int r = (tid >> 2) + 64 * j;
-        const int gr = min(row0 + r, seg_hi - 1);
-        a_src[j] = p.A + (size_t)gr * rowbytes + part * 16;
-        a_dst[j] = part * SUB_A + r * 16;
-    }
-    const uint8_t* b_src[2];
-    int b_dst[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-        const int br = (tid >> 2) + 64 * j;
-        const int wrow = GATEUP ? (j == 0 ? n0 + br : I_up + n0 + (br - 64)) : n0 + br;
-        b_src[j] = p.W + ((size_t)e * p.w_rows + wrow) * rowbytes + part * 16;
-        b_dst[j] = REGION_A + part * SUB_B + br * 16;
-    }
-
-    // ---- FP4: all scale bytes of the tile's rows, one dword per row per K-step
-    uint32_t* sc = reinterpret_cast<uint32_t*>(smem + 2 * STAGE_BYTES);
+    const int kd = p.K >> 7;                              // FP4: scale dwords per row (one per K-step)
+    const int kdl = kd > 1 ? 32 - __clz(kd - 1) : 0;      //      rounded up to a power of two
+    const size_t srow = (size_t)(p.K >> 5);
     const int spd = (int)lds_scale_stride_dwords(p.K);
-    if constexpr (FP4) {
-        const int kd = p.K >> 7;
-        const size_t srow = (size_t)(p.K >> 5);
-        for (int idx = tid; idx < (BM + BNW) * kd; idx += 256) {
-            const int row = idx / kd, d = idx - row * kd;
-            const uint8_t* src;
-            if (row < BM) {
-                src = p.As + (size_t)min(row0 + row, seg_hi - 1) * srow;
-            } else {
-                const int br = row - BM;
-                const int wrow = GATEUP ? (br < 64 ? n0 + br : I_up + n0 + (br - 64)) : n0 + br;
-                src = p.Ws + ((size_t)e * p.w_rows + wrow) * srow;
-            }
-            sc[row * spd + d] = *reinterpret_cast<const uint32_t*>(src + 4 * d);
-        }
+    uint32_t* sc = reinterpret_cast<uint32_t*>(smem + 2 * G::STAGE);
+
+    // ---- tile-independent: LDS destinations of this thread's 16-byte chunks (4 per 64-byte row
+    //      segment) and the fragment / scale addresses of this lane
+    const int part = tid & 3;
+    int a_dst[G::JA], b_dst[G::JB];
+#pragma unroll
+    for (int j = 0; j < G::JA; ++j) a_dst[j] = part * G::SUB_A + ((tid >> 2) + (NT / 4) * j) * 16;
+#pragma unroll
+    for (int j = 0; j < G::JB; ++j) b_dst[j] = G::REGION_A + part * G::SUB_B + w_slot((tid >> 2) + (NT / 4) * j) * 16;
+    int b_rows[WN];                                       // first weight-tile row of each of this wave's column tiles
+#pragma unroll
+    for (int t = 0; t < WN; ++t) {
+        if constexpr (GATEUP) b_rows[t] = (t < WN / 2 ? 0 : G::GC) + wn * (WN / 2) * 32 + (t % (WN / 2)) * 32;
+        else b_rows[t] = wn * WN * 32 + t * 32;
     }
-
-    v16f_t acc[4][2];
+    const int a_frag = half * G::SUB_A + (wm * 128 + li) * 16;                 // + mt*512 + slice*2*SUB_A
+    int b_frag[WN], sb_idx[WN];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-    // ---- software pipeline: LDS holds K-step ks (double buffered), registers hold K-step ks+1,
-    //      whose global loads were issued a whole iteration earlier; the scheduling barriers keep
-    //      the LDS refill and the next loads BEHIND the iteration's MFMAs.
-    u32x4_t ga[4], gb[2];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) ga[j] = *reinterpret_cast<const u32x4_t*>(a_src[j]);
-#pragma unroll
-    for (int j = 0; j < 2; ++j) gb[j] = *reinterpret_cast<const u32x4_t*>(b_src[j]);
-#pragma unroll
-    for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4_t*>(smem + a_dst[j]) = ga[j];
-#pragma unroll
-    for (int j = 0; j < 2; ++j) *reinterpret_cast<u32x4_t*>(smem + b_dst[j]) = gb[j];
-    if (nks > 1) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) ga[j] = *reinterpret_cast<const u32x4_t*>(a_src[j] + KSTEP_BYTES);
-#pragma unroll
-        for (int j = 0; j < 2; ++j) gb[j] = *reinterpret_cast<const u32x4_t*>(b_src[j] + KSTEP_BYTES);
+    for (int t = 0; t < WN; ++t) {
+        b_frag[t] = G::REGION_A + half * G::SUB_B + (b_rows[t] + li) * 16;     // + slice*2*SUB_B
+        sb_idx[t] = (BM + b_rows[t] + w_row_of_lane(li)) * spd;
     }
-    __syncthreads();
-
-    // fragment addresses inside a stage
-    const int a_frag = half * SUB_A + (wm * 128 + li) * 16;                    // + mt*512 + slice*2*SUB_A
-    const int b_row0 = GATEUP ? wn * 32 : wn * 64;                             // tile 0 rows
-    const int b_row1 = GATEUP ? 64 + wn * 32 : wn * 64 + 32;                   // tile 1 rows
-    const int b_frag0 = REGION_A + half * SUB_B + (b_row0 + li) * 16;          // + slice*2*SUB_B
-    const int b_frag1 = REGION_A + half * SUB_B + (b_row1 + li) * 16;
     const int sa_idx = (wm * 128 + li) * spd;                                  // + mt*32*spd + ks
-    const int sb_idx0 = (BM + b_row0 + li) * spd;
-    const int sb_idx1 = (BM + b_row1 + li) * spd;
     const int sshift = half * 8;
 
-    for (int ks = 0; ks < nks; ++ks) {
-        const uint8_t* st = smem + (ks & 1) * STAGE_BYTES;
-        int sa[4] = {0, 0, 0, 0}, sb[2] = {0, 0};
-        if constexpr (FP4) {
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt) sa[mt] = (int)(sc[sa_idx + mt * 32 * spd + ks] >> sshift);
-            sb[0] = (int)(sc[sb_idx0 + ks] >> sshift);
-            sb[1] = (int)(sc[sb_idx1 + ks] >> sshift);
-        }
-        u32x4_t fa0[4], fb0[2], fa1[4], fb1[2];
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) fa0[mt] = *reinterpret_cast<const u32x4_t*>(st + a_frag + mt * 512);
-        fb0[0] = *reinterpret_cast<const u32x4_t*>(st + b_frag0);
-        fb0[1] = *reinterpret_cast<const u32x4_t*>(st + b_frag1);
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) fa1[mt] = *reinterpret_cast<const u32x4_t*>(st + 2 * SUB_A + a_frag + mt * 512);
-        fb1[0] = *reinterpret_cast<const u32x4_t*>(st + 2 * SUB_B + b_frag0);
-        fb1[1] = *reinterpret_cast<const u32x4_t*>(st + 2 * SUB_B + b_frag1);
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {                     // K-slice 0: scale bytes 0/1 of the K-step's dword
-            mma<FP4, 0>(acc[mt][0], fa0[mt], fb0[0], sa[mt], sb[0]);
-            mma<FP4, 0>(acc[mt][1], fa0[mt], fb0[1], sa[mt], sb[1]);
-        }
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {                     // K-slice 1: scale bytes 2/3
-            mma<FP4, 2>(acc[mt][0], fa1[mt], fb1[0], sa[mt], sb[0]);
-            mma<FP4, 2>(acc[mt][1], fa1[mt], fb1[1], sa[mt], sb[1]);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if (ks + 1 < nks) {
-            uint8_t* nx = smem + ((ks + 1) & 1) * STAGE_BYTES;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) *reinterpret_cast<u32x4_t*>(nx + a_dst[j]) = ga[j];
-#pragma unroll
-            for (int j = 0; j < 2; ++j) *reinterpret_cast<u32x4_t*>(nx + b_dst[j]) = gb[j];
-        }
-        __builtin_amdgcn_sched_barrier(0);
-        if (ks + 2 < nks) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j) ga[j] = *reinterpret_cast<const u32x4_t*>(a_src[j] + (size_t)(ks + 2) * KSTEP_BYTES);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) gb[j] = *reinterpret_cast<const u32x4_t*>(b_src[j] + (size_t)(ks + 2) * KSTEP_BYTES);
-        }
-        __syncthreads();
-    }
+    // ---- per-tile prefetch state: source pointers and the first K-step
+    const uint8_t* a_src[G::JA];
+    const uint8_t* b_src[G::JB];
+    u32x4_t ga[G::JA], gb[G::JB];
+    TileInfo ti = decode_tile(p, tile, COLS);
 
-    // ---- epilogue.  acc[mt][nt][r] is row mt*32 + (r/4)*8 + half*4 + r%4 of the wave's 128,
-    //      column li of the wave's nt-th 32-column tile.  The operand stages are free now.
-    const int rows_valid = seg_hi - row0;                 // rows of this tile that exist (may exceed BM)
-    if constexpr (GATEUP) {
-        uint8_t* hst = smem;                               // [256][HST] bf16 h tile
+    auto prefetch_tile = [&](const TileInfo& t) {
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt)
+        for (int j = 0; j < G::JA; ++j) {
+            const int gr = min(t.row0 + (tid >> 2) + (NT / 4) * j, t.seg_hi - 1);
+            a_src[j] = p.A + (size_t)gr * rowbytes + part * 16;
+        }
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const float g = acc[mt][0][r], u = acc[mt][1][r];
-                const float h = g * u / (1.0f + __expf(-g));
-                const int row = wm * 128 + mt * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-                *reinterpret_cast<uint16_t*>(hst + row * HST + (wn * 32 + li) * 2) = f32_to_bf16_rne(h);
-            }
-        __syncthreads();
+        for (int j = 0; j < G::JB; ++j) {
+            const int br = (tid >> 2) + (NT / 4) * j;
+            b_src[j] = p.W + ((size_t)t.e * p.w_rows + w_tile_row<GATEUP, G::GC>(br, t.n0, I_up)) * rowbytes + part * 16;
+        }
+#pragma unroll
+        for (int j = 0; j < G::JA; ++j) ga[j] = *reinterpret_cast<const u32x4_t*>(a_src[j]);
+#pragma unroll
+        for (int j = 0; j < G::JB; ++j) gb[j] = *reinterpret_cast<const u32x4_t*>(b_src[j]);
+    };
+    prefetch_tile(ti);
+
+    while (true) {
+        // ---- scales and the prefetched first K-step go to LDS, K-step 1 starts
         if constexpr (FP4) {
-            const size_t qrow = (size_t)(p.n_out >> 1), srow = (size_t)(p.n_out >> 5);
+            // all scale bytes of the tile's rows, one dword per row per K-step: the whole batch is
+            // in flight together (not prefetched across the epilogue: the registers are not there)
+            uint32_t sv[SBATCH];
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const int u = tid + 256 * j;
-                const int row = u >> 1, blk = u & 1;
-                u32x4_t v[4];
+            for (int u = 0; u < SBATCH; ++u) {
+                const int idx = u * NT + tid;
+                const int row = idx >> kdl, d = idx & ((1 << kdl) - 1);
+                sv[u] = 0;
+                if (row < BM + G::BNW && d < kd) {
+                    const uint8_t* src = row < BM
+                        ? p.As + (size_t)min(ti.row0 + row, ti.seg_hi - 1) * srow
+                        : p.Ws + ((size_t)ti.e * p.w_rows + w_tile_row<GATEUP, G::GC>(row - BM, ti.n0, I_up)) * srow;
+                    sv[u] = *reinterpret_cast<const uint32_t*>(src + 4 * d);
+                }
+            }
 #pragma unroll
-                for (int q = 0; q < 4; ++q) v[q] = *reinterpret_cast<const u32x4_t*>(hst + row * HST + blk * 64 + q * 16);
-                uint32_t byte;
-                const u32x4_t codes = encode_block_lane(v, &byte);
-                if (row < rows_valid) {
-                    *reinterpret_cast<u32x4_t*>(p.out + (size_t)(row0 + row) * qrow + (n0 >> 1) + blk * 16) = codes;
-                    p.outs[(size_t)(row0 + row) * srow + (n0 >> 5) + blk] = (uint8_t)byte;
+            for (int u = 0; u < SBATCH; ++u) {
+                const int idx = u * NT + tid;
+                const int row = idx >> kdl, d = idx & ((1 << kdl) - 1);
+                if (row < BM + G::BNW && d < kd) sc[row * spd + d] = sv[u];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < G::JA; ++j) *reinterpret_cast<u32x4_t*>(smem + a_dst[j]) = ga[j];
+#pragma unroll
+        for (int j = 0; j < G::JB; ++j) *reinterpret_cast<u32x4_t*>(smem + b_dst[j]) = gb[j];
+        if (nks > 1) {
+#pragma unroll
+            for (int j = 0; j < G::JA; ++j) ga[j] = *reinterpret_cast<const u32x4_t*>(a_src[j] + KSTEP_BYTES);
+#pragma unroll
+            for (int j = 0; j < G::JB; ++j) gb[j] = *reinterpret_cast<const u32x4_t*>(b_src[j] + KSTEP_BYTES);
+        }
+        __syncthreads();
+
+        v16f_t acc[4][WN];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < WN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+        // ---- main loop: LDS holds K-step ks (double buffered), registers hold K-step ks+1,
+        //      whose global loads were issued a whole iteration earlier.
+        for (int ks = 0; ks < nks; ++ks) {
+            const uint8_t* st = smem + (ks & 1) * G::STAGE;
+            int sa[4] = {0, 0, 0, 0}, sb[WN];
+#pragma unroll
+            for (int t = 0; t < WN; ++t) sb[t] = 0;
+            if constexpr (FP4) {
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt) sa[mt] = (int)(sc[sa_idx + mt * 32 * spd + ks] >> sshift);
+#pragma unroll
+                for (int t = 0; t < WN; ++t) sb[t] = (int)(sc[sb_idx[t] + ks] >> sshift);
+            }
+            u32x4_t fa0[4], fb0[WN], fa1[4], fb1[WN];
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) fa0[mt] = *reinterpret_cast<const u32x4_t*>(st + a_frag + mt * 512);
+#pragma unroll
+            for (int t = 0; t < WN; ++t) fb0[t] = *reinterpret_cast<const u32x4_t*>(st + b_frag[t]);
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) fa1[mt] = *reinterpret_cast<const u32x4_t*>(st + 2 * G::SUB_A + a_frag + mt * 512);
+#pragma unroll
+            for (int t = 0; t < WN; ++t) fb1[t] = *reinterpret_cast<const u32x4_t*>(st + 2 * G::SUB_B + b_frag[t]);
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)                   // K-slice 0: scale bytes 0/1 of the K-step's dword
+#pragma unroll
+                for (int t = 0; t < WN; ++t) mma<FP4, 0>(acc[mt][t], fb0[t], fa0[mt], sb[t], sa[mt]);
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt)                   // K-slice 1: scale bytes 2/3
+#pragma unroll
+                for (int t = 0; t < WN; ++t) mma<FP4, 2>(acc[mt][t], fb1[t], fa1[mt], sb[t], sa[mt]);
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks + 1 < nks) {
+                uint8_t* nx = smem + ((ks + 1) & 1) * G::STAGE;
+#pragma unroll
+                for (int j = 0; j < G::JA; ++j) *reinterpret_cast<u32x4_t*>(nx + a_dst[j]) = ga[j];
+#pragma unroll
+                for (int j = 0; j < G::JB; ++j) *reinterpret_cast<u32x4_t*>(nx + b_dst[j]) = gb[j];
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (ks + 2 < nks) {
+#pragma unroll
+                for (int j = 0; j < G::JA; ++j) ga[j] = *reinterpret_cast<const u32x4_t*>(a_src[j] + (size_t)(ks + 2) * KSTEP_BYTES);
+#pragma unroll
+                for (int j = 0; j < G::JB; ++j) gb[j] = *reinterpret_cast<const u32x4_t*>(b_src[j] + (size_t)(ks + 2) * KSTEP_BYTES);
+            }
+            __syncthreads();
+        }
+
+        // ---- the block's next tile: get its first K-step moving before the epilogue
+        const TileInfo cur = ti;
+        const bool more = PERSIST && tile + nslots < tile_hi;
+        if (more) {
+            tile += nslots;
+            ti = decode_tile(p, tile, COLS);
+            prefetch_tile(ti);
+        }
+
+        // ---- epilogue, straight from registers.  acc[mt][t][r] belongs to activation row
+        //      wm*128 + mt*32 + li and to column 16*half + r of the wave's t-th 32-column tile.
+        const int rows_valid = cur.seg_hi - cur.row0;     // rows of this tile that exist (may exceed BM)
+        const int row0 = cur.row0, n0 = cur.n0;
+        if constexpr (GATEUP) {
+            constexpr int HT = WN / 2;                     // h column tiles per wave
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+                const int m = wm * 128 + mt * 32 + li;
+                const bool valid = m < rows_valid;
+                const size_t grow = (size_t)(row0 + m);
+#pragma unroll
+                for (int t = 0; t < HT; ++t) {
+                    const int ctile = n0 + wn * HT * 32 + t * 32;  // first h column of the 32-column tile
+                    uint32_t hb[8];                                // 16 BF16 values: columns ctile + 16*half + 0..15
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        const float g0 = acc[mt][t][2 * q], u0 = acc[mt][t + HT][2 * q];
+                        const float g1 = acc[mt][t][2 * q + 1], u1 = acc[mt][t + HT][2 * q + 1];
+                        hb[q] = pack_bf16x2(g0 * u0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)),
+                                            g1 * u1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)));
+                    }
+                    if constexpr (FP4) {
+                        const u32x4_t v0 = {hb[0], hb[1], hb[2], hb[3]}, v1 = {hb[4], hb[5], hb[6], hb[7]};
+                        uint32_t amax = max(amax_bits8(v0), amax_bits8(v1));
+                        amax = max(amax, (uint32_t)__shfl_xor((int)amax, 32));    // the block's other 16 columns
+                        const uint32_t byte = e8m0_from_amax(amax);
+                        const float scl = scale_operand(byte);
+                        const u32x2_t codes = {encode8(v0, scl), encode8(v1, scl)};
+                        if (valid) {
+                            *reinterpret_cast<u32x2_t*>(p.out + grow * (size_t)(p.n_out >> 1) + (ctile >> 1) + half * 8) = codes;
+                            if (half == 0) p.outs[grow * (size_t)(p.n_out >> 5) + (ctile >> 5)] = (uint8_t)byte;
+                        }
+                    } else if (valid) {
+                        u32x4_t* dst = reinterpret_cast<u32x4_t*>(p.out + (grow * (size_t)p.n_out + ctile + half * 16) * 2);
+                        dst[0] = u32x4_t{hb[0], hb[1], hb[2], hb[3]};
+                        dst[1] = u32x4_t{hb[4], hb[5], hb[6], hb[7]};
+                    }
                 }
             }
         } else {
-            const size_t orow = (size_t)p.n_out * 2;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int c = tid + 256 * j;
-                const int row = c >> 3, pc = c & 7;
-                if (row < rows_valid)
-                    *reinterpret_cast<u32x4_t*>(p.out + (size_t)(row0 + row) * orow + (size_t)n0 * 2 + pc * 16) =
-                        *reinterpret_cast<const u32x4_t*>(hst + row * HST + pc * 16);
+            for (int mt = 0; mt < 4; ++mt) {
+                const int m = wm * 128 + mt * 32 + li;
+                if (m < rows_valid) {
+#pragma unroll
+                    for (int t = 0; t < WN; ++t) {
+                        const int col = n0 + wn * WN * 32 + t * 32 + half * 16;
+                        u32x4_t* dst = reinterpret_cast<u32x4_t*>(p.out + ((size_t)(row0 + m) * p.n_out + col) * 2);
+                        dst[0] = u32x4_t{pack_bf16x2(acc[mt][t][0], acc[mt][t][1]), pack_bf16x2(acc[mt][t][2], acc[mt][t][3]),
+                                         pack_bf16x2(acc[mt][t][4], acc[mt][t][5]), pack_bf16x2(acc[mt][t][6], acc[mt][t][7])};
+                        dst[1] = u32x4_t{pack_bf16x2(acc[mt][t][8], acc[mt][t][9]), pack_bf16x2(acc[mt][t][10], acc[mt][t][11]),
+                                         pack_bf16x2(acc[mt][t][12], acc[mt][t][13]), pack_bf16x2(acc[mt][t][14], acc[mt][t][15])};
+                    }
+                }
             }
         }
-    } else {
-        uint8_t* yst = smem;                               // [128][YST] bf16, one 128-row half at a time
-        const size_t orow = (size_t)p.n_out * 2;
-#pragma unroll
-        for (int hm = 0; hm < 2; ++hm) {
-            if (wm == hm) {
-#pragma unroll
-                for (int mt = 0; mt < 4; ++mt)
-#pragma unroll
-                    for (int t2 = 0; t2 < 2; ++t2)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) {
-                            const int row = mt * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-                            *reinterpret_cast<uint16_t*>(yst + row * YST + (wn * 64 + t2 * 32 + li) * 2) = f32_to_bf16_rne(acc[mt][t2][r]);
-                        }
-            }
-            __syncthreads();
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int c = tid + 256 * j;
-                const int row = c >> 4, pc = c & 15;
-                if (hm * 128 + row < rows_valid)
-                    *reinterpret_cast<u32x4_t*>(p.out + (size_t)(row0 + hm * 128 + row) * orow + (size_t)n0 * 2 + pc * 16) =
-                        *reinterpret_cast<const u32x4_t*>(yst + row * YST + pc * 16);
-            }
-            __syncthreads();
-        }
+        if (!more) break;
     }
 }
 
-template <bool FP4, bool GATEUP>
-static int launch_gemm(const GemmParams& p, long long max_rows, hipStream_t s) {
-    const size_t scale_bytes = FP4 ? (size_t)(BM + BNW) * lds_scale_stride_dwords(p.K) * 4 : 0;
-    const size_t lds = 2 * (size_t)STAGE_BYTES + scale_bytes;        // the epilogue staging (<= 36.9 KB) aliases the stages
+// Block tile choices (selector g_tile): 2 = 256x128, 4 waves, two blocks per CU;
+// 8 = 256x256, 8 waves of 128x64, one block per CU.
+template <bool FP4, bool GATEUP, int WN, int WGN, int MINB>
+static int launch_gemm_geo(GemmParams p, long long max_rows, int num_cus, hipStream_t s) {
+    using G = Geo<WN, WGN>;
+    p.n_tiles_n = GATEUP ? p.n_out / G::GC : p.n_out / G::BNW;
+    const size_t scale_bytes = FP4 ? (size_t)(BM + G::BNW) * lds_scale_stride_dwords(p.K) * 4 : 0;
+    const size_t lds = 2 * (size_t)G::STAGE + scale_bytes;
+    const size_t lds_cap = MINB == 2 ? 80 * 1024 : 160 * 1024;
     static bool attr_done = false;                                   // per instantiation
     if (!attr_done) {
-        REALB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_gemm_kernel<FP4, GATEUP>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 / 2));
+        REALB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_gemm_kernel<FP4, GATEUP, WN, WGN, MINB>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_cap));
         attr_done = true;
     }
     const long long m_tiles_max = (max_rows + BM - 1) / BM + p.n_local;
     const long long total_max = m_tiles_max * p.n_tiles_n;
-    const long long grid = 8 * ((total_max + 7) / 8);
+    const long long slots = 8ll * (((long long)num_cus * MINB + 7) / 8);   // one block per residency slot, multiple of 8 (XCDs)
+    const long long all_tiles = 8 * ((total_max + 7) / 8);
+    const long long grid = (FP4 || total_max < slots) ? all_tiles : slots;                // FP4: one tile per block
     REALB_REQUIRE(grid < (1ll << 31), REALB_ECAP, "too many tiles");
-    REALB_REQUIRE(lds <= 80 * 1024, REALB_ESHAPE, "K=%d needs %zu bytes of LDS", p.K, lds);
-    hipLaunchKernelGGL((ffn_gemm_kernel<FP4, GATEUP>), dim3((unsigned)grid), dim3(256), lds, s, p);
+    REALB_REQUIRE(FP4 ? p.K <= 2048 : true, REALB_ESHAPE, "FP4 path supports K <= 2048 (K=%d)", p.K);
+    REALB_REQUIRE(lds <= lds_cap, REALB_ESHAPE, "K=%d needs %zu bytes of LDS", p.K, lds);
+    hipLaunchKernelGGL((ffn_gemm_kernel<FP4, GATEUP, WN, WGN, MINB>), dim3((unsigned)grid), dim3(G::NT), lds, s, p);
     REALB_HIP(hipGetLastError());
     return REALB_OK;
+}
+
+static int g_tile = 0;    // 0 = automatic; 2 or 8 forces a geometry (set through realb_set_gemm_tile)
+
+template <bool FP4, bool GATEUP>
+static int launch_gemm(const GemmParams& p, long long max_rows, int num_cus, hipStream_t s) {
+    const int unit256 = GATEUP ? 128 : 256;             // output columns per block of the 256-wide tile
+    const bool can256 = p.n_out % unit256 == 0;
+    const int sel = !can256 ? 2 : (g_tile == 0 ? (FP4 ? 2 : 8) : g_tile);   // measured: BF16 prefers the 256-wide tile
+    if (sel == 8) return launch_gemm_geo<FP4, GATEUP, 2, 4, 1>(p, max_rows, num_cus, s);
+    return launch_gemm_geo<FP4, GATEUP, 2, 2, 2>(p, max_rows, num_cus, s);
 }
 
 }  // namespace realb
 
 using namespace realb;
+
+extern "C" int realb_set_gemm_tile(int wn) {
+    REALB_REQUIRE(wn == 0 || wn == 2 || wn == 8, REALB_EINVAL, "tile selector must be 0, 2 or 8");
+    g_tile = wn;
+    return REALB_OK;
+}
 
 static int ffn_stages(realb_ctx* ctx, int prec, int stages, const int32_t* expert_offsets, int n_local, long long max_rows,
                       const void* x, const uint8_t* x_s, const void* w13, const uint8_t* w13_s, const void* w2,
@@ -346,15 +440,15 @@ static int ffn_stages(realb_ctx* ctx, int prec, int stages, const int32_t* exper
                   "NULL scale tensor on the FP4 path");
     const int H = c->cfg.H, I = c->cfg.I;
     hipStream_t s = as_stream(stream);
-    GemmParams g1{(const uint8_t*)x, x_s, (const uint8_t*)w13, w13_s, (uint8_t*)h_mid, h_s, expert_offsets, n_local, H, 2 * I, I, I / 64};
-    GemmParams g2{(const uint8_t*)h_mid, h_s, (const uint8_t*)w2, w2_s, (uint8_t*)y_rows, nullptr, expert_offsets, n_local, I, H, H, H / 128};
+    GemmParams g1{(const uint8_t*)x, x_s, (const uint8_t*)w13, w13_s, (uint8_t*)h_mid, h_s, expert_offsets, n_local, H, 2 * I, I, 0};
+    GemmParams g2{(const uint8_t*)h_mid, h_s, (const uint8_t*)w2, w2_s, (uint8_t*)y_rows, nullptr, expert_offsets, n_local, I, H, H, 0};
     int rc = REALB_OK;
     if (prec == REALB_FP4) {
-        if (s1) rc = launch_gemm<true, true>(g1, max_rows, s);
-        if (rc == REALB_OK && s2) rc = launch_gemm<true, false>(g2, max_rows, s);
+        if (s1) rc = launch_gemm<true, true>(g1, max_rows, c->num_cus, s);
+        if (rc == REALB_OK && s2) rc = launch_gemm<true, false>(g2, max_rows, c->num_cus, s);
     } else {
-        if (s1) rc = launch_gemm<false, true>(g1, max_rows, s);
-        if (rc == REALB_OK && s2) rc = launch_gemm<false, false>(g2, max_rows, s);
+        if (s1) rc = launch_gemm<false, true>(g1, max_rows, c->num_cus, s);
+        if (rc == REALB_OK && s2) rc = launch_gemm<false, false>(g2, max_rows, c->num_cus, s);
     }
     return rc;
 }

@@ -287,6 +287,33 @@ def test_ffn_fp4(R, case):
     assert rel_fro(out, o["out"]) <= 2 * FP4_TOL
 
 
+@pytest.mark.parametrize("tile", [8])
+def test_ffn_other_block_tiles_give_the_same_rows(R, case, tile):
+    """The 256x256 block tile (8 waves) produces bit-identical outputs to the default
+    tile: the per-element FP32 accumulation order along K does not depend on the tile."""
+    from paper_2604_19503_amd.binding import set_gemm_tile
+    b = case.buf
+    for prec in (R.BF16, R.FP4):
+        _say(f"ffn tile={tile} prec={prec} {case.name}")
+        set_gemm_tile(2)
+        _run_path(R, case, prec)
+        Rr = int(b.expert_offsets[-1])
+        ref_y = b.y_rows[:Rr].clone()
+        ref_h = b.h_mid.view(torch.int16).clone()
+        ref_hs = b.h_s.clone()
+        try:
+            set_gemm_tile(tile)
+            b.h_mid.zero_()
+            _run_path(R, case, prec)
+        finally:
+            set_gemm_tile(0)
+        n_h = Rr * case.cfg.I // (4 if prec == R.FP4 else 1)          # int16 words of h actually written
+        assert torch.equal(b.y_rows[:Rr].view(torch.int16), ref_y.view(torch.int16))
+        assert torch.equal(b.h_mid.view(torch.int16).reshape(-1)[:n_h], ref_h.reshape(-1)[:n_h])
+        if prec == R.FP4:
+            assert torch.equal(b.h_s[:Rr], ref_hs[:Rr])
+
+
 # ---------------------------------------------------------------------------- whole layer
 @pytest.mark.parametrize("force", [0, 1])
 def test_layer_forward_matches_step_calls_and_is_deterministic(R, case, force):
