@@ -20,6 +20,7 @@ struct Ctx {
     // device workspace
     int32_t* wave_cnt;     // [n_chunks_max, n_local]  per-chunk local-expert counts, then exclusive bases
     int n_chunks_max;
+    int32_t* hist_part;    // [num_cus, 2*E]  per-block partial histograms of route_stats
     // pinned host staging for the policy's inputs
     int32_t* stats_host;   // [2*D]
     hipStream_t side;      // side stream for the weight encoder

@@ -94,12 +94,13 @@ int realb_create(const realb_config* cfg, realb_ctx** out) {
     c->cfg = *cfg;
     c->n_local = cfg->E / cfg->D;
     c->M = cfg->M_init;
-    c->wave_cnt = nullptr; c->stats_host = nullptr; c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr;
+    c->wave_cnt = nullptr; c->hist_part = nullptr; c->stats_host = nullptr; c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr;
     hipError_t e = hipGetDevice(&c->device);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&c->num_cus, hipDeviceAttributeMultiprocessorCount, c->device);
     long long A_max = (long long)cfg->T_max * cfg->k;
     c->n_chunks_max = ceil_div(A_max, kPermChunk) + 1;
     if (e == hipSuccess) e = hipMalloc((void**)&c->wave_cnt, (size_t)c->n_chunks_max * c->n_local * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void**)&c->hist_part, (size_t)c->num_cus * 2 * cfg->E * sizeof(int32_t));
     if (e == hipSuccess) e = hipHostMalloc((void**)&c->stats_host, 2 * cfg->D * sizeof(int32_t), hipHostMallocDefault);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
@@ -116,6 +117,7 @@ int realb_destroy(realb_ctx* ctx) {
     if (!ctx) return REALB_OK;
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     if (c->wave_cnt) (void)hipFree(c->wave_cnt);
+    if (c->hist_part) (void)hipFree(c->hist_part);
     if (c->stats_host) (void)hipHostFree(c->stats_host);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);

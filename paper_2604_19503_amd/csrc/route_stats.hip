@@ -7,11 +7,6 @@
 
 namespace realb {
 
-// Clears the two histograms (and is the only writer of them before the main kernel).
-__global__ void zero_hist_kernel(int32_t* a, int32_t* b, int n) {
-    for (int i = threadIdx.x; i < n; i += blockDim.x) { a[i] = 0; b[i] = 0; }
-}
-
 // DPP lane exchange inside a row of 16 lanes (no LDS traffic).
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float v) {
@@ -44,12 +39,12 @@ __device__ __forceinline__ float wave_max(float v) {
 // One wave per token.  Lane l holds the EPL consecutive experts l*EPL .. l*EPL+EPL-1,
 // so that among equal logits the lowest (lane, slot) is the lowest expert index.
 // k rounds of: per-lane best -> wave maximum -> lowest lane holding it wins.
-// The block's histograms live in LDS and are flushed with integer atomics.
+// The block's histograms live in LDS; each block writes its partial histogram to the workspace
+// (no global atomics, no pre-zeroing), and a one-block kernel adds the partials up.
 template <int EPL>
-__global__ void __launch_bounds__(256) topk_hist_kernel(const float* __restrict__ logits, const uint8_t* __restrict__ is_vision,
+__global__ void __launch_bounds__(1024) topk_hist_kernel(const float* __restrict__ logits, const uint8_t* __restrict__ is_vision,
                                                         int T, int E, int k, int32_t* __restrict__ topk_ids,
-                                                        float* __restrict__ topk_w, int32_t* __restrict__ expert_cnt,
-                                                        int32_t* __restrict__ expert_vis) {
+                                                        float* __restrict__ topk_w, int32_t* __restrict__ hist_part) {
     extern __shared__ int32_t hist[];                 // [2*E]: counts, vision counts
     for (int i = threadIdx.x; i < 2 * E; i += blockDim.x) hist[i] = 0;
     __syncthreads();
@@ -94,25 +89,37 @@ __global__ void __launch_bounds__(256) topk_hist_kernel(const float* __restrict_
         }
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < E; i += blockDim.x) {
-        if (hist[i]) atomicAdd(&expert_cnt[i], hist[i]);
-        if (hist[E + i]) atomicAdd(&expert_vis[i], hist[E + i]);
-    }
+    for (int i = threadIdx.x; i < 2 * E; i += blockDim.x) hist_part[(size_t)blockIdx.x * 2 * E + i] = hist[i];
 }
 
-// Per-rank sums of the finished histograms (a separate launch: a kernel boundary is the
-// cheap way to make the atomics of all XCDs visible; a device-scope fence per block is not).
-__global__ void rank_sums_kernel(const int32_t* __restrict__ expert_cnt, const int32_t* __restrict__ expert_vis,
-                                 int D, int n_local, int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis) {
-    const int d = threadIdx.x;
-    if (d >= D) return;
-    int load = 0, vis = 0;
-    for (int e = 0; e < n_local; ++e) {
-        load += expert_cnt[d * n_local + e];
-        vis += expert_vis[d * n_local + e];
+// Adds up the blocks' partial histograms and the per-rank sums (a separate launch: the kernel
+// boundary makes the partials of all XCDs visible).  Thread layout: counter c = tid % CW,
+// slice = tid / CW; each slice walks its share of the partials, LDS atomics merge the slices.
+__global__ void __launch_bounds__(1024) hist_reduce_kernel(const int32_t* __restrict__ hist_part, int n_part, int E, int D,
+                                                           int32_t* __restrict__ expert_cnt, int32_t* __restrict__ expert_vis,
+                                                           int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis) {
+    extern __shared__ int32_t tot[];                  // [2*E]
+    const int C2 = 2 * E;
+    for (int i = threadIdx.x; i < C2; i += blockDim.x) tot[i] = 0;
+    __syncthreads();
+    int cw = 1;
+    while (cw < C2) cw <<= 1;                         // counters per slice row, power of two, <= 1024
+    const int n_slices = blockDim.x / cw;
+    const int c = threadIdx.x % cw, slice = threadIdx.x / cw;
+    if (c < C2 && slice < n_slices) {
+        int sum = 0;
+        for (int b = slice; b < n_part; b += n_slices) sum += hist_part[(size_t)b * C2 + c];
+        if (sum) atomicAdd(&tot[c], sum);
     }
-    rank_load[d] = load;
-    rank_vis[d] = vis;
+    __syncthreads();
+    for (int i = threadIdx.x; i < E; i += blockDim.x) { expert_cnt[i] = tot[i]; expert_vis[i] = tot[E + i]; }
+    const int n_local = E / D;
+    for (int d = threadIdx.x; d < D; d += blockDim.x) {
+        int load = 0, vis = 0;
+        for (int e = 0; e < n_local; ++e) { load += tot[d * n_local + e]; vis += tot[E + d * n_local + e]; }
+        rank_load[d] = load;
+        rank_vis[d] = vis;
+    }
 }
 
 }  // namespace realb
@@ -128,21 +135,22 @@ extern "C" int realb_route_stats(realb_ctx* ctx, const float* logits, const uint
     REALB_REQUIRE(T == 0 || (logits && is_vision && topk_ids && topk_w), REALB_EINVAL, "NULL argument");
     hipStream_t s = as_stream(stream);
     const int E = c->cfg.E, k = c->cfg.k, D = c->cfg.D;
-    hipLaunchKernelGGL(zero_hist_kernel, dim3(1), dim3(256), 0, s, expert_cnt, expert_vis, E);
+    int blocks = 0;
     if (T > 0) {
-        const int blocks = min(ceil_div(T, 4), 256 * 8);
+        blocks = min(ceil_div(T, 16), c->num_cus);          // 16 waves (tokens in flight) per block
         const size_t lds = 2 * (size_t)E * sizeof(int32_t);
         const int epl = ceil_div(E, 64);
-#define REALB_TOPK(EPL)                                                                                        \
-    hipLaunchKernelGGL(topk_hist_kernel<EPL>, dim3(blocks), dim3(256), lds, s, logits, is_vision, T, E, k, \
-                       topk_ids, topk_w, expert_cnt, expert_vis)
+#define REALB_TOPK(EPL)                                                                                      \
+    hipLaunchKernelGGL(topk_hist_kernel<EPL>, dim3(blocks), dim3(1024), lds, s, logits, is_vision, T, E, k, \
+                       topk_ids, topk_w, c->hist_part)
         if (epl == 1) REALB_TOPK(1);
         else if (epl == 2) REALB_TOPK(2);
         else if (epl <= 4) REALB_TOPK(4);
         else REALB_TOPK(8);
 #undef REALB_TOPK
     }
-    hipLaunchKernelGGL(rank_sums_kernel, dim3(1), dim3(64), 0, s, expert_cnt, expert_vis, D, c->n_local, rank_load, rank_vis);
+    hipLaunchKernelGGL(hist_reduce_kernel, dim3(1), dim3(1024), 2 * (size_t)E * sizeof(int32_t), s, c->hist_part, blocks, E, D,
+                       expert_cnt, expert_vis, rank_load, rank_vis);
     REALB_HIP(hipGetLastError());
     return REALB_OK;
 }
