@@ -38,6 +38,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true")
     ap.add_argument("--gemm-tile", type=int, default=0, choices=[0, 2, 8], help="grouped-GEMM block tile selector (0 = automatic)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 512 MiB device copy (untimed) so that a counter run can scale FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--detail", default=None, help="write the per-kernel breakdown (JSON) to this path")
     return ap.parse_args()
 
@@ -170,6 +172,19 @@ def main():
     else:
         roofline = {"kernel": dom, "bound": "hbm", "achieved": d["rate"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
                     "frac": d["rate"] / PEAK_HBM_GBS, "traffic": None, "ms": d["ms"]}
+
+    # measured HBM traffic of the dominant kernel, if a counter summary for this workload is committed
+    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(traffic_file):
+        with open(traffic_file) as f:
+            roofline["traffic"] = json.load(f).get(f"{args.workload}_{args.precision}_{dom}")
+    if args.calibrate_copy:
+        src = torch.ones(128 << 20, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)                      # 512 MiB read + 512 MiB written per launch
+        torch.cuda.synchronize()
+        del src, dst
 
     ffn_ms = stages["ffn_gate_up"]["ms"] + stages["ffn_down"]["ms"]
     extra = {

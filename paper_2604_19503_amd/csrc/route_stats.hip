@@ -108,6 +108,7 @@ __global__ void __launch_bounds__(1024) hist_reduce_kernel(const int32_t* __rest
     const int c = threadIdx.x % cw, slice = threadIdx.x / cw;
     if (c < C2 && slice < n_slices) {
         int sum = 0;
+#pragma unroll 8
         for (int b = slice; b < n_part; b += n_slices) sum += hist_part[(size_t)b * C2 + c];
         if (sum) atomicAdd(&tot[c], sum);
     }
