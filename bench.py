@@ -11,6 +11,15 @@ rank's experts), forced to the FP4 path.  Prints ONE JSON line.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c1]
                   [--no-cpu-baseline] [--detail PATH]
+
+Two further reports (each prints its own JSON line; weights are drawn on the device,
+N(0, 0.02), because only timing is taken):
+  --workload c4   8 simulated EP ranks run one after the other on the one GPU, 20 seeded
+                  iterations with the vision skew redrawn, AIMD state carried: max-over-ranks
+                  layer time, all-BF16 versus the policy's mixed-precision plan.
+  --workload c5   48 layers with distinct BF16 weight sets on a Qwen3-VL-shaped rank, 65536
+                  tokens: per-layer time with the weight encoding on the side stream, on the
+                  main stream, and skipped (weights encoded beforehand) -> exposed encoding time.
 """
 from __future__ import annotations
 
@@ -33,7 +42,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"],
+                    help="c2 (default) is the headline line; c4 = 8-rank imbalance simulation, c5 = 48-layer overlap stress")
     ap.add_argument("--precision", default="fp4", choices=["fp4", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true")
@@ -97,6 +107,147 @@ def cpu_baseline(cfg, inp, prec_fp4: bool, budget_s: float = 12.0):
                       f"{done} of the rank's {nl} experts ({rows} rows), {dt:.1f} s", "seconds": dt, "rows": rows}
 
 
+def _device_weights(torch, n, H, I, seed):
+    g = torch.Generator(device="cuda")
+    g.manual_seed(seed)
+    w13 = (torch.randn((n, 2 * I, H), generator=g, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+    w2 = (torch.randn((n, H, I), generator=g, device="cuda", dtype=torch.float32) * 0.02).to(torch.bfloat16)
+    return w13, w2
+
+
+def run_c4(args):
+    """Simulated 8-rank EP imbalance (latency objective T_MoE = max_i T_i of the paper's
+    problem formulation): every rank's share runs serially on the one GPU."""
+    import numpy as np
+    import torch
+    import workloads as W
+    import paper_2604_19503_amd as R
+    from paper_2604_19503_amd.binding import default_config
+    cfg = W.CONFIGS["c4"]
+    iters = 20
+    rcfg = default_config(cfg.T, cfg.E, cfg.k, cfg.D, cfg.H, cfg.I)
+    ctx = R.Context(rcfg)
+    buf = R.LayerBuffers(rcfg, cfg.T)
+    xb, isv_np = W.gen_tokens(cfg, 0)
+    x = R.bf16_from_bits(xb)
+    isv = torch.from_numpy(isv_np).cuda()
+    weights = [_device_weights(torch, cfg.n_local, cfg.H, cfg.I, 100 + d) for d in range(cfg.D)]
+    reps = max(1, min(args.steps, 5))
+    per_iter = []
+    ctx.M = rcfg.M_init
+    for it in range(iters):
+        logits_np, info = W.gen_logits_c4(cfg, it, isv_np)
+        lg = torch.from_numpy(logits_np).cuda()
+        ctx.route_stats(lg, isv, buf)
+        prec, ib, M = ctx.select_precision(buf, cfg.T)
+        load = buf.rank_load.cpu().numpy()
+        vis = buf.rank_vis.cpu().numpy()
+        t_bf16, t_plan = [], []
+        for d in range(cfg.D):
+            w13, w2 = weights[d]
+            io = ctx.make_io(lg, isv, x, w13, w2, buf, d, overlap=True)
+            for which, p in (("bf16", R.BF16), ("plan", int(prec[d]))):
+                if which == "plan" and p == R.BF16:
+                    t_plan.append(t_bf16[-1])
+                    continue
+                ctx.rank_forward(io, p)                      # warm-up
+                avg, _ = event_ms(lambda: ctx.rank_forward(io, p), reps, torch)
+                (t_bf16 if which == "bf16" else t_plan).append(avg)
+        per_iter.append({"iteration": it, "kind": info["kind"], "hot_rank": info["hot_rank"], "ib_global": round(ib, 3),
+                         "M": M, "fp4_ranks": [int(d) for d in np.nonzero(prec)[0]],
+                         "rank_vision_share": [round(float(v) / max(int(l), 1), 3) for v, l in zip(vis, load)],
+                         "rank_ms_bf16": [round(t, 4) for t in t_bf16], "rank_ms_plan": [round(t, 4) for t in t_plan],
+                         "max_ms_bf16": max(t_bf16), "max_ms_plan": max(t_plan),
+                         "straggler_bf16": int(np.argmax(t_bf16)), "straggler_plan": int(np.argmax(t_plan))})
+    mb = float(np.mean([p["max_ms_bf16"] for p in per_iter]))
+    mp = float(np.mean([p["max_ms_plan"] for p in per_iter]))
+    best = max(p["max_ms_bf16"] / p["max_ms_plan"] for p in per_iter)
+    result = {"metric": "max-rank MoE layer ms (mean over 20 iterations of max over 8 simulated ranks), mixed-precision plan",
+              "value": mp, "unit": "ms", "n_gpus": 1, "steps": iters, "warmup": 1, "ms_per_step": mp,
+              "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16 / fp4 per rank (policy)",
+              "data": "synthetic",
+              "config": {"workload": "c4: Kimi-VL-shaped layer, 64 experts top-6, 8 ranks x 8 experts run serially, T=16384, "
+                                     "70% vision, skew redrawn per iteration, AIMD carried"},
+              "extra": {"max_rank_ms_all_bf16": mb, "max_rank_ms_plan": mp, "mean_speedup": mb / mp, "best_iteration_speedup": best,
+                        "iterations_with_fp4": sum(1 for p in per_iter if p["fp4_ranks"]),
+                        "paper_context": "paper: average MoE layer latency 1.51 -> 1.36 ms, rank-level up to 1.29x (8x RTX 5090)"}}
+    if args.detail:
+        with open(args.detail, "w") as f:
+            json.dump({"result": result, "iterations": per_iter}, f, indent=1)
+    ctx.close()
+    print(json.dumps(result))
+
+
+def run_c5(args):
+    """Overlap stress: how much of the on-the-fly weight transformation stays exposed when it
+    runs on the side stream under the permutation (the paper hides it under dispatch)."""
+    import numpy as np
+    import torch
+    import workloads as W
+    import paper_2604_19503_amd as R
+    from paper_2604_19503_amd.binding import default_config
+    cfg = W.CONFIGS["c5"]
+    layers = 48
+    rcfg = default_config(cfg.T, cfg.E, cfg.k, cfg.D, cfg.H, cfg.I)
+    ctx = R.Context(rcfg)
+    buf = R.LayerBuffers(rcfg, cfg.T)
+    xb, isv_np = W.gen_tokens(cfg, 0)
+    x = R.bf16_from_bits(xb)
+    isv = torch.from_numpy(isv_np).cuda()
+    lg = torch.from_numpy(W.gen_logits(cfg, 0, isv_np)).cuda()
+    weights = [_device_weights(torch, cfg.n_local, cfg.H, cfg.I, 200 + l) for l in range(layers)]
+    ios = {mode: [ctx.make_io(lg, isv, x, w13, w2, buf, cfg.rank, force=R.FP4, overlap=mode) for (w13, w2) in weights]
+           for mode in (0, 1)}
+
+    def sweep(mode):
+        for l in range(layers):
+            ctx.layer_forward(ios[mode][l])
+
+    def timed(mode):
+        sweep(mode)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(max(1, min(args.steps, 5))):
+            sweep(mode)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / (layers * max(1, min(args.steps, 5)))
+
+    ms_overlap = timed(1)
+    ms_seq = timed(0)
+    # weights encoded beforehand: one layer's buffers reused (the GEMMs read the same bytes each time)
+    io2 = ctx.make_io(lg, isv, x, weights[0][0], weights[0][1], buf, cfg.rank, force=R.FP4, overlap=0)
+    ctx.layer_forward(io2)
+    io2.overlap = 2
+    torch.cuda.synchronize()
+    reps = layers * max(1, min(args.steps, 5))
+    ctx.layer_forward(io2)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(reps):
+        ctx.layer_forward(io2)
+    torch.cuda.synchronize()
+    ms_noquant = (time.perf_counter() - t0) * 1e3 / reps
+    qms, _ = event_ms(lambda: ctx.quantize_experts_fp4(weights[1][0], weights[1][1], buf), 20, torch)
+    n_w = cfg.n_local * 3 * cfg.H * cfg.I
+    rows = int(buf.expert_offsets[-1].item())
+    result = {"metric": "per-layer ms over 48 layers of distinct weights, FP4 path, weight encoding on the side stream",
+              "value": ms_overlap, "unit": "ms", "n_gpus": 1, "steps": layers, "warmup": layers, "ms_per_step": ms_overlap,
+              "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+              "dtype": "fp4 (MXFP4 E2M1 + E8M0/32, fp32 accumulate)", "data": "synthetic",
+              "config": {"workload": "c5: Qwen3-VL-shaped rank, 128 experts top-8, 16 local, H=2048 I=768, T=65536 tokens, "
+                                     "85% vision, 48 distinct BF16 weight sets"},
+              "extra": {"rows_on_rank": rows, "layer_ms_overlap": ms_overlap, "layer_ms_sequential": ms_seq,
+                        "layer_ms_weights_pre_encoded": ms_noquant, "exposed_encoding_ms_overlap": ms_overlap - ms_noquant,
+                        "exposed_encoding_ms_sequential": ms_seq - ms_noquant, "encoder_alone_ms": qms,
+                        "encoder_alone_gbs": n_w * 2.53125 / (qms * 1e-3) / 1e9,
+                        "paper_context": "paper: hiding the transformation is worth 3% end to end (ReaLB vs ReaLB-seq)"}}
+    if args.detail:
+        with open(args.detail, "w") as f:
+            json.dump({"result": result}, f, indent=1)
+    ctx.close()
+    print(json.dumps(result))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -116,6 +267,10 @@ def main():
     if args.gemm_tile:
         from paper_2604_19503_amd.binding import set_gemm_tile
         set_gemm_tile(args.gemm_tile)
+    if args.workload == "c4":
+        return run_c4(args)
+    if args.workload == "c5":
+        return run_c5(args)
     cfg = W.CONFIGS[args.workload]
     fp4 = args.precision == "fp4"
     force = R.FP4 if fp4 else R.BF16

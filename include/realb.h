@@ -179,7 +179,9 @@ typedef struct {
     /* inputs */
     const float* logits; const uint8_t* is_vision; const void* x; int T;
     const void* w13; const void* w2;            /* this rank's BF16 expert weights */
-    int rank; int force; int overlap;           /* overlap != 0: weight encoding on the context's side stream */
+    int rank; int force;
+    int overlap;                                /* weight encoding: 0 = on `stream`, 1 = on the context's side stream,
+                                                   2 = skipped (w13_q .. w2_s already hold this layer's encoded weights) */
     long long max_rows;
     /* outputs / workspaces (caller-allocated) */
     int32_t* topk_ids; float* topk_w; int32_t* expert_cnt; int32_t* expert_vis;

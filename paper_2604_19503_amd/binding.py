@@ -246,7 +246,9 @@ class Context:
         _check(self.lib.realb_combine(self._h, _p(b.y_rows), _p(b.assign_to_row), _p(b.topk_w), b.T, _p(b.out), _stream(stream)))
 
     def make_io(self, logits, is_vision, x, w13, w2, b: LayerBuffers, rank: int, force: int = FORCE_NONE,
-                overlap: bool = True) -> LayerIO:
+                overlap=True) -> LayerIO:
+        """overlap: 0/False = weight encoding on the call's stream, 1/True = on the context's side stream,
+        2 = skipped (the buffers already hold this layer's encoded weights)."""
         io = LayerIO()
         g = lambda t: None if t is None else t.data_ptr()
         io.logits, io.is_vision, io.x, io.T = g(logits), g(is_vision), g(x), x.shape[0]

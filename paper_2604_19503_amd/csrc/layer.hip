@@ -14,9 +14,10 @@ extern "C" int realb_rank_forward(realb_ctx* ctx, realb_layer_io* io, int prec, 
     hipStream_t s = as_stream(stream);
     int rc;
     const bool fp4 = prec == REALB_FP4;
-    if (fp4) {
-        REALB_REQUIRE(io->w13_q && io->w13_s && io->w2_q && io->w2_s, REALB_EINVAL, "NULL FP4 weight buffer");
-        if (io->overlap) {
+    const bool side = io->overlap == 1;
+    if (fp4) REALB_REQUIRE(io->w13_q && io->w13_s && io->w2_q && io->w2_s, REALB_EINVAL, "NULL FP4 weight buffer");
+    if (fp4 && io->overlap != 2) {
+        if (side) {
             REALB_HIP(hipEventRecord(c->ev_fork, s));
             REALB_HIP(hipStreamWaitEvent(c->side, c->ev_fork, 0));
             rc = realb_quantize_experts_fp4(ctx, io->w13, io->w2, c->n_local, io->w13_q, io->w13_s, io->w2_q, io->w2_s, c->side);
@@ -30,7 +31,7 @@ extern "C" int realb_rank_forward(realb_ctx* ctx, realb_layer_io* io, int prec, 
     rc = realb_permute(ctx, io->x, io->topk_ids, io->T, io->rank, prec, io->max_rows, io->expert_offsets, io->row_to_assign,
                        io->assign_to_row, io->x_perm, io->x_q, io->x_s, stream);
     if (rc != REALB_OK) return rc;
-    if (fp4 && io->overlap) REALB_HIP(hipStreamWaitEvent(s, c->ev_join, 0));
+    if (fp4 && side) REALB_HIP(hipStreamWaitEvent(s, c->ev_join, 0));
     if (fp4)
         rc = realb_grouped_moe_ffn(ctx, prec, io->expert_offsets, c->n_local, io->max_rows, io->x_q, io->x_s, io->w13_q,
                                    io->w13_s, io->w2_q, io->w2_s, io->h_mid, io->h_s, io->y_rows, stream);
