@@ -18,7 +18,14 @@
  *   - FP4 tensors are OCP MXFP4: 4-bit E2M1 codes (bit 3 sign; magnitudes
  *     0,.5,1,1.5,2,3,4,6), two per byte with the even element in the low nibble,
  *     plus one E8M0 scale byte (2^(byte-127)) per block of 32 consecutive elements
- *     along the contraction dimension.  The paper's NVFP4 (blocks of 16, E4M3
+ *     along the contraction dimension.  Scale tensors are K-STEP TILED, the order in
+ *     which the block-scaled MFMA consumes them: for a matrix [rows, K] (K a multiple
+ *     of 128, KD = K/128) the byte of (row, block kb) is at
+ *         (((row/32)*KD + kb/4)*32 + row%32)*4 + kb%4,
+ *     i.e. the 4 scales of one row at one 128-element K-step form a dword and 32
+ *     consecutive rows are contiguous; the tensor covers ceil(rows/32)*32 rows, so a
+ *     scale buffer "u8 [rows, K/32]" below holds ceil(rows/32)*32*K/32 bytes.  Weight
+ *     tensors [n_local, N, K] count as n_local*N rows.  The paper's NVFP4 (blocks of 16, E4M3
  *     scale, global scale) is mapped onto this format because gfx950's
  *     block-scaled matrix instructions take E8M0 scales.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
@@ -116,8 +123,8 @@ int realb_select_precision_host(const realb_config* cfg, const int32_t* rank_loa
 int realb_quantize_experts_fp4(realb_ctx* ctx, const void* w13, const void* w2, int n_local,
                                uint8_t* w13_q, uint8_t* w13_s, uint8_t* w2_q, uint8_t* w2_s, void* stream);
 
-/* The same encoder on any BF16 matrix [rows, K] (K multiple of 32): q u8 [rows,K/2],
- * s u8 [rows,K/32].  No context needed. */
+/* The same encoder on any BF16 matrix [rows, K] (K multiple of 128): q u8 [rows,K/2],
+ * s u8 [rows,K/32] (K-step tiled).  No context needed. */
 int realb_quantize_rows_fp4(const void* x, long long rows, int K, uint8_t* q, uint8_t* s, void* stream);
 
 /* Token permutation / dispatch packing for rank `rank` (the local stand-in for

@@ -107,6 +107,18 @@ def bf16_from_bits(bits: np.ndarray, device="cuda") -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device).view(torch.bfloat16)
 
 
+def scales_to_canonical(s, rows: int, K: int) -> np.ndarray:
+    """Pure index permutation (no arithmetic): a K-step-tiled scale tensor, as the library reads
+    and writes it, rearranged to the plain [rows, K/32] order.  Byte (row, kb) of the tiled tensor
+    sits at (((row//32)*KD + kb//4)*32 + row%32)*4 + kb%4 with KD = K/128."""
+    flat = (s.detach().cpu().numpy() if isinstance(s, torch.Tensor) else np.asarray(s)).reshape(-1)
+    KD = K // 128
+    row = np.arange(rows, dtype=np.int64)[:, None]
+    kb = np.arange(K // 32, dtype=np.int64)[None, :]
+    idx = (((row >> 5) * KD + (kb >> 2)) * 32 + (row & 31)) * 4 + (kb & 3)
+    return flat[idx]
+
+
 def bits_from_bf16(t: torch.Tensor) -> np.ndarray:
     return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
 
@@ -133,10 +145,11 @@ def select_precision_host(cfg: Config, rank_load, rank_vis, T: int, M: float, fo
 
 
 def quantize_rows_fp4(x: torch.Tensor, stream=None):
-    """realb_quantize_rows_fp4 on a bf16 [rows,K] tensor -> (q u8 [rows,K/2], s u8 [rows,K/32])."""
+    """realb_quantize_rows_fp4 on a bf16 [rows,K] tensor -> (q u8 [rows,K/2], s u8 K-step-tiled,
+    ceil(rows/32)*32 * K/32 bytes; see scales_to_canonical)."""
     rows, K = x.shape
     q = torch.empty((rows, K // 2), dtype=torch.uint8, device=x.device)
-    s = torch.empty((rows, K // 32), dtype=torch.uint8, device=x.device)
+    s = torch.zeros((-(-rows // 32) * 32, K // 32), dtype=torch.uint8, device=x.device)
     _check(load_library().realb_quantize_rows_fp4(_p(x), rows, K, _p(q), _p(s), _stream(stream)))
     return q, s
 
@@ -165,13 +178,14 @@ class LayerBuffers:
         self.assign_to_row = torch.empty(max(1, T * k), **i32)
         self.x_perm = torch.empty((R, H), **bf)
         self.x_q = torch.empty((R, H // 2), **u8)
-        self.x_s = torch.empty((R, H // 32), **u8)
+        R32 = -(-R // 32) * 32                           # scale tensors cover whole groups of 32 rows
+        self.x_s = torch.empty((R32, H // 32), **u8)
         self.w13_q = torch.empty((nl, 2 * I, H // 2), **u8)
         self.w13_s = torch.empty((nl, 2 * I, H // 32), **u8)
         self.w2_q = torch.empty((nl, H, I // 2), **u8)
         self.w2_s = torch.empty((nl, H, I // 32), **u8)
         self.h_mid = torch.empty((R, I), **bf)          # FP4 path uses its first R*I/2 bytes as codes
-        self.h_s = torch.empty((R, I // 32), **u8)
+        self.h_s = torch.empty((R32, I // 32), **u8)
         self.y_rows = torch.empty((R, H), **bf)
         self.out = torch.empty((T, H), **bf)
 

@@ -72,8 +72,6 @@ struct GemmParams {
     int n_tiles_n;           // column tiles (I/GC or H/BNW)
 };
 
-__host__ __device__ __forceinline__ size_t lds_scale_stride_dwords(int K) { return (size_t)((K >> 7) | 1); }
-
 // acc += W_tile (A operand, 32 weight rows) x X_tile^T (B operand, 32 activation rows)
 template <bool FP4, int OPSEL>
 __device__ __forceinline__ void mma(v16f_t& acc, const u32x4_t& w, const u32x4_t& x, int sw, int sx) {
@@ -139,7 +137,6 @@ __global__ void __launch_bounds__(128 * WGN, MINB) ffn_gemm_kernel(const GemmPar
     constexpr int NT = G::NT;
     constexpr int COLS = GATEUP ? G::GC : G::BNW;
     constexpr bool PERSIST = !FP4;    // the FP4 body has no registers to spare for a tile carried across the epilogue
-    constexpr int SBATCH = FP4 ? (BM + G::BNW) * 16 / NT : 1;         // scale dwords per thread (covers K <= 2048 at once)
     extern __shared__ __align__(16) uint8_t smem[];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -159,11 +156,9 @@ __global__ void __launch_bounds__(128 * WGN, MINB) ffn_gemm_kernel(const GemmPar
     const int I_up = p.w_rows >> 1;                       // gate/up: offset of the up rows
     const size_t rowbytes = FP4 ? (size_t)(p.K >> 1) : (size_t)p.K * 2;
     const int nks = (int)(rowbytes / KSTEP_BYTES);
-    const int kd = p.K >> 7;                              // FP4: scale dwords per row (one per K-step)
-    const int kdl = kd > 1 ? 32 - __clz(kd - 1) : 0;      //      rounded up to a power of two
-    const size_t srow = (size_t)(p.K >> 5);
-    const int spd = (int)lds_scale_stride_dwords(p.K);
-    uint32_t* sc = reinterpret_cast<uint32_t*>(smem + 2 * G::STAGE);
+    const int kd = p.K >> 7;                              // FP4: K-steps = scale dwords per row
+    const uint32_t* As32 = reinterpret_cast<const uint32_t*>(p.As);
+    const uint32_t* Ws32 = reinterpret_cast<const uint32_t*>(p.Ws);
 
     // ---- tile-independent: LDS destinations of this thread's 16-byte chunks (4 per 64-byte row
     //      segment) and the fragment / scale addresses of this lane
@@ -180,19 +175,20 @@ __global__ void __launch_bounds__(128 * WGN, MINB) ffn_gemm_kernel(const GemmPar
         else b_rows[t] = wn * WN * 32 + t * 32;
     }
     const int a_frag = half * G::SUB_A + (wm * 128 + li) * 16;                 // + mt*512 + slice*2*SUB_A
-    int b_frag[WN], sb_idx[WN];
+    int b_frag[WN];
 #pragma unroll
-    for (int t = 0; t < WN; ++t) {
-        b_frag[t] = G::REGION_A + half * G::SUB_B + (b_rows[t] + li) * 16;     // + slice*2*SUB_B
-        sb_idx[t] = (BM + b_rows[t] + w_row_of_lane(li)) * spd;
-    }
-    const int sa_idx = (wm * 128 + li) * spd;                                  // + mt*32*spd + ks
+    for (int t = 0; t < WN; ++t) b_frag[t] = G::REGION_A + half * G::SUB_B + (b_rows[t] + li) * 16;   // + slice*2*SUB_B
     const int sshift = half * 8;
 
     // ---- per-tile prefetch state: source pointers and the first K-step
     const uint8_t* a_src[G::JA];
     const uint8_t* b_src[G::JB];
     u32x4_t ga[G::JA], gb[G::JB];
+    // FP4: dword index (K-step 0) of this lane's scale words in the K-step-tiled scale tensors; a
+    // wave's 32 rows at one K-step are one contiguous 128-byte line (two when the rows straddle
+    // a group of 32), so the scales go from memory to the MFMA operand registers directly.
+    int sa_off[4], sb_off[WN];
+    uint32_t sa_nx[4], sb_nx[WN];                         // scale words of the next K-step
     TileInfo ti = decode_tile(p, tile, COLS);
 
     auto prefetch_tile = [&](const TileInfo& t) {
@@ -210,34 +206,25 @@ __global__ void __launch_bounds__(128 * WGN, MINB) ffn_gemm_kernel(const GemmPar
         for (int j = 0; j < G::JA; ++j) ga[j] = *reinterpret_cast<const u32x4_t*>(a_src[j]);
 #pragma unroll
         for (int j = 0; j < G::JB; ++j) gb[j] = *reinterpret_cast<const u32x4_t*>(b_src[j]);
+        if constexpr (FP4) {
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+                const int row = min(t.row0 + wm * 128 + mt * 32 + li, t.seg_hi - 1);
+                sa_off[mt] = ((row >> 5) * kd) * 32 + (row & 31);
+                sa_nx[mt] = As32[sa_off[mt]];
+            }
+#pragma unroll
+            for (int c = 0; c < WN; ++c) {
+                const int wrow = t.e * p.w_rows + w_tile_row<GATEUP, G::GC>(b_rows[c] + w_row_of_lane(li), t.n0, I_up);
+                sb_off[c] = ((wrow >> 5) * kd) * 32 + (wrow & 31);
+                sb_nx[c] = Ws32[sb_off[c]];
+            }
+        }
     };
     prefetch_tile(ti);
 
     while (true) {
         // ---- scales and the prefetched first K-step go to LDS, K-step 1 starts
-        if constexpr (FP4) {
-            // all scale bytes of the tile's rows, one dword per row per K-step: the whole batch is
-            // in flight together (not prefetched across the epilogue: the registers are not there)
-            uint32_t sv[SBATCH];
-#pragma unroll
-            for (int u = 0; u < SBATCH; ++u) {
-                const int idx = u * NT + tid;
-                const int row = idx >> kdl, d = idx & ((1 << kdl) - 1);
-                sv[u] = 0;
-                if (row < BM + G::BNW && d < kd) {
-                    const uint8_t* src = row < BM
-                        ? p.As + (size_t)min(ti.row0 + row, ti.seg_hi - 1) * srow
-                        : p.Ws + ((size_t)ti.e * p.w_rows + w_tile_row<GATEUP, G::GC>(row - BM, ti.n0, I_up)) * srow;
-                    sv[u] = *reinterpret_cast<const uint32_t*>(src + 4 * d);
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < SBATCH; ++u) {
-                const int idx = u * NT + tid;
-                const int row = idx >> kdl, d = idx & ((1 << kdl) - 1);
-                if (row < BM + G::BNW && d < kd) sc[row * spd + d] = sv[u];
-            }
-        }
 #pragma unroll
         for (int j = 0; j < G::JA; ++j) *reinterpret_cast<u32x4_t*>(smem + a_dst[j]) = ga[j];
 #pragma unroll
@@ -267,9 +254,15 @@ __global__ void __launch_bounds__(128 * WGN, MINB) ffn_gemm_kernel(const GemmPar
             for (int t = 0; t < WN; ++t) sb[t] = 0;
             if constexpr (FP4) {
 #pragma unroll
-                for (int mt = 0; mt < 4; ++mt) sa[mt] = (int)(sc[sa_idx + mt * 32 * spd + ks] >> sshift);
+                for (int mt = 0; mt < 4; ++mt) sa[mt] = (int)(sa_nx[mt] >> sshift);
 #pragma unroll
-                for (int t = 0; t < WN; ++t) sb[t] = (int)(sc[sb_idx[t] + ks] >> sshift);
+                for (int t = 0; t < WN; ++t) sb[t] = (int)(sb_nx[t] >> sshift);
+                if (ks + 1 < nks) {
+#pragma unroll
+                    for (int mt = 0; mt < 4; ++mt) sa_nx[mt] = As32[sa_off[mt] + (ks + 1) * 32];
+#pragma unroll
+                    for (int t = 0; t < WN; ++t) sb_nx[t] = Ws32[sb_off[t] + (ks + 1) * 32];
+                }
             }
             u32x4_t fa0[4], fb0[WN], fa1[4], fb1[WN];
 #pragma unroll
@@ -346,7 +339,7 @@ __global__ void __launch_bounds__(128 * WGN, MINB) ffn_gemm_kernel(const GemmPar
                         const u32x2_t codes = {encode8(v0, scl), encode8(v1, scl)};
                         if (valid) {
                             *reinterpret_cast<u32x2_t*>(p.out + grow * (size_t)(p.n_out >> 1) + (ctile >> 1) + half * 8) = codes;
-                            if (half == 0) p.outs[grow * (size_t)(p.n_out >> 5) + (ctile >> 5)] = (uint8_t)byte;
+                            if (half == 0) p.outs[scale_byte_offset((long long)grow, ctile >> 5, p.n_out >> 7)] = (uint8_t)byte;
                         }
                     } else if (valid) {
                         u32x4_t* dst = reinterpret_cast<u32x4_t*>(p.out + (grow * (size_t)p.n_out + ctile + half * 16) * 2);
@@ -382,8 +375,7 @@ template <bool FP4, bool GATEUP, int WN, int WGN, int MINB>
 static int launch_gemm_geo(GemmParams p, long long max_rows, int num_cus, hipStream_t s) {
     using G = Geo<WN, WGN>;
     p.n_tiles_n = GATEUP ? p.n_out / G::GC : p.n_out / G::BNW;
-    const size_t scale_bytes = FP4 ? (size_t)(BM + G::BNW) * lds_scale_stride_dwords(p.K) * 4 : 0;
-    const size_t lds = 2 * (size_t)G::STAGE + scale_bytes;
+    const size_t lds = 2 * (size_t)G::STAGE;
     const size_t lds_cap = MINB == 2 ? 80 * 1024 : 160 * 1024;
     static bool attr_done = false;                                   // per instantiation
     if (!attr_done) {
@@ -397,7 +389,6 @@ static int launch_gemm_geo(GemmParams p, long long max_rows, int num_cus, hipStr
     const long long all_tiles = 8 * ((total_max + 7) / 8);
     const long long grid = (FP4 || total_max < slots) ? all_tiles : slots;                // FP4: one tile per block
     REALB_REQUIRE(grid < (1ll << 31), REALB_ECAP, "too many tiles");
-    REALB_REQUIRE(FP4 ? p.K <= 2048 : true, REALB_ESHAPE, "FP4 path supports K <= 2048 (K=%d)", p.K);
     REALB_REQUIRE(lds <= lds_cap, REALB_ESHAPE, "K=%d needs %zu bytes of LDS", p.K, lds);
     hipLaunchKernelGGL((ffn_gemm_kernel<FP4, GATEUP, WN, WGN, MINB>), dim3((unsigned)grid), dim3(G::NT), lds, s, p);
     REALB_HIP(hipGetLastError());

@@ -17,6 +17,15 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(2))) unsigned short u16x2_t;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4_t;
 
+// Where a scale byte lives.  Scale tensors are "K-step tiled" so that the block-scaled MFMA can
+// fetch them straight from memory: for a matrix [rows, K] with KD = K/128 K-steps, the 4 scale
+// bytes of (row, K-step) form one dword, and the dwords of 32 consecutive rows at one K-step are
+// contiguous (128 bytes):   byte(row, kb) at (((row/32)*KD + kb/4)*32 + row%32)*4 + kb%4.
+// The tensor covers ceil(rows/32)*32 rows.
+__host__ __device__ __forceinline__ size_t scale_byte_offset(long long row, int kb, int KD) {
+    return ((((size_t)(row >> 5) * KD + (kb >> 2)) * 32 + (row & 31)) << 2) + (kb & 3);
+}
+
 // max |.| of the two BF16 halves of each of 4 dwords, as a 15-bit integer pattern.
 __device__ __forceinline__ uint32_t amax_bits8(const u32x4_t& v) {
     u16x2_t a = __builtin_bit_cast(u16x2_t, v.x & 0x7FFF7FFFu);

@@ -141,7 +141,7 @@ __global__ void __launch_bounds__(256) perm_gather_kernel(const u32x4_t* __restr
                 if (c < chunks) {
                     if (FP4) {
                         x_q[(size_t)r * chunks + c] = codes[u];
-                        if ((lane & 3) == 0) x_s[(size_t)r * (chunks >> 2) + (c >> 2)] = (uint8_t)byte[u];
+                        if ((lane & 3) == 0) x_s[scale_byte_offset(r, c >> 2, chunks >> 4)] = (uint8_t)byte[u];
                     } else {
                         x_perm[(size_t)r * chunks + c] = v[u];
                     }

@@ -1,47 +1,55 @@
 // On-the-fly BF16 -> MXFP4 weight transformation (paper Sec. "Overhead-Aware
 // Pipeline Orchestration", Overlapping Pipeline): a pure HBM stream, 2 B read
-// and 17/32 B written per element.
+// and 17/32 B written per element.  Scale bytes go to their K-step-tiled positions.
 #include "common.h"
 #include "mxfp4_device.h"
 
 namespace realb {
 
-// The tensor is a flat sequence of 32-element blocks (rows are multiples of 32
-// long and contiguous).  A quad of lanes encodes one block: each lane loads 16 B
-// (8 values), the quad shares the maximum, each lane stores 4 B of codes and the
-// quad's first lane stores the scale byte.  UNROLL independent loads per lane
-// keep enough bytes in flight.
+// The tensor is a flat sequence of 32-element blocks (rows are multiples of 128 long and
+// contiguous).  A quad of lanes encodes one block: each lane loads 16 B (8 values), the quad
+// shares the maximum, each lane stores 4 B of codes and the quad's first lane stores the scale
+// byte at its K-step-tiled position.  UNROLL independent loads per lane keep enough bytes in flight.
 template <int UNROLL>
 __global__ void __launch_bounds__(256) quantize_flat_kernel(const u32x4_t* __restrict__ src, uint32_t* __restrict__ q,
-                                                            uint8_t* __restrict__ s, long long n_chunks) {
-    const long long base = ((long long)blockIdx.x * UNROLL) * 256 + threadIdx.x;
+                                                            uint8_t* __restrict__ s, long long n_chunks, int cpr,
+                                                            float inv_cpr) {
+    const long long block_base = ((long long)blockIdx.x * UNROLL) * 256;
+    const int KD = cpr >> 4;                                  // K-steps per row (128 elements = 16 chunks)
+    const unsigned row_b = (unsigned)block_base / (unsigned)cpr;             // one division per thread; n_chunks < 2^31
+    const int in_row0 = (int)((unsigned)block_base - row_b * (unsigned)cpr);
     u32x4_t v[UNROLL];
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
-        long long c = base + (long long)u * 256;
+        const long long c = block_base + (long long)u * 256 + threadIdx.x;
         v[u] = c < n_chunks ? __builtin_nontemporal_load(src + c) : u32x4_t{0, 0, 0, 0};
     }
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
-        long long c = base + (long long)u * 256;
+        const long long cb = block_base + (long long)u * 256;     // uniform: first chunk of this pass
+        const long long c = cb + threadIdx.x;
         uint32_t byte;
-        uint32_t codes = encode_block_quad(v[u], &byte);      // whole quads are in or out of range together
+        const uint32_t codes = encode_block_quad(v[u], &byte);    // whole quads are in or out of range together
         if (c < n_chunks) {
             __builtin_nontemporal_store(codes, q + c);
-            if ((threadIdx.x & 3) == 0) s[c >> 2] = (uint8_t)byte;
+            if ((threadIdx.x & 3) == 0) {
+                const int in_row = in_row0 + u * 256 + threadIdx.x;                  // < cpr + 1024
+                const int dr = (int)(((float)in_row + 0.5f) * inv_cpr);              // exact: in_row < 2^16
+                s[scale_byte_offset(row_b + dr, (in_row - dr * cpr) >> 2, KD)] = (uint8_t)byte;
+            }
         }
     }
 }
 
-int launch_quantize_flat(const void* src, long long n_elems, uint8_t* q, uint8_t* s, hipStream_t stream) {
-    if (n_elems == 0) return REALB_OK;
+int launch_quantize_flat(const void* src, long long rows, int K, uint8_t* q, uint8_t* s, hipStream_t stream) {
+    if (rows == 0) return REALB_OK;
     constexpr int UNROLL = 4;
-    const long long n_chunks = n_elems / 8;                   // n_elems is a multiple of 32
+    const long long n_chunks = rows * (K / 8);
     const long long per_block = 256ll * UNROLL;
     const long long blocks = (n_chunks + per_block - 1) / per_block;
-    REALB_REQUIRE(blocks < (1ll << 31), REALB_ECAP, "tensor too large for one launch");
+    REALB_REQUIRE(n_chunks < (1ll << 31), REALB_ECAP, "tensor too large for one launch");
     hipLaunchKernelGGL(quantize_flat_kernel<UNROLL>, dim3((unsigned)blocks), dim3(256), 0, stream,
-                       (const u32x4_t*)src, (uint32_t*)q, s, n_chunks);
+                       (const u32x4_t*)src, (uint32_t*)q, s, n_chunks, K / 8, 1.0f / (float)(K / 8));
     REALB_HIP(hipGetLastError());
     return REALB_OK;
 }
@@ -53,10 +61,10 @@ using namespace realb;
 extern "C" {
 
 int realb_quantize_rows_fp4(const void* x, long long rows, int K, uint8_t* q, uint8_t* s, void* stream) {
-    REALB_REQUIRE(rows >= 0 && K > 0 && K % 32 == 0, REALB_ESHAPE, "rows=%lld K=%d: K must be a positive multiple of 32", rows, K);
+    REALB_REQUIRE(rows >= 0 && K > 0 && K % 128 == 0 && K <= 65536, REALB_ESHAPE, "rows=%lld K=%d: K must be a positive multiple of 128", rows, K);
     if (rows == 0) return REALB_OK;
     REALB_REQUIRE(x && q && s, REALB_EINVAL, "NULL argument");
-    return launch_quantize_flat(x, rows * K, q, s, as_stream(stream));
+    return launch_quantize_flat(x, rows, K, q, s, as_stream(stream));
 }
 
 int realb_quantize_experts_fp4(realb_ctx* ctx, const void* w13, const void* w2, int n_local, uint8_t* w13_q,
@@ -64,11 +72,9 @@ int realb_quantize_experts_fp4(realb_ctx* ctx, const void* w13, const void* w2, 
     REALB_REQUIRE(ctx && w13 && w2 && w13_q && w13_s && w2_q && w2_s, REALB_EINVAL, "NULL argument");
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     REALB_REQUIRE(n_local >= 0 && n_local <= c->n_local, REALB_ECAP, "n_local=%d exceeds the context's %d", n_local, c->n_local);
-    const long long n13 = (long long)n_local * 2 * c->cfg.I * c->cfg.H;
-    const long long n2 = (long long)n_local * c->cfg.H * c->cfg.I;
-    int rc = launch_quantize_flat(w13, n13, w13_q, w13_s, as_stream(stream));
+    int rc = launch_quantize_flat(w13, (long long)n_local * 2 * c->cfg.I, c->cfg.H, w13_q, w13_s, as_stream(stream));
     if (rc != REALB_OK) return rc;
-    return launch_quantize_flat(w2, n2, w2_q, w2_s, as_stream(stream));
+    return launch_quantize_flat(w2, (long long)n_local * c->cfg.H, c->cfg.I, w2_q, w2_s, as_stream(stream));
 }
 
 }  // extern "C"

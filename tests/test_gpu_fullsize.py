@@ -83,20 +83,23 @@ def test_full_size_layer(name):
         if force == R.FP4:
             xq_tok, xs_tok = omx.quantize_packed(inp["x"])                       # encode per token, gather = encode per row
             assert np.array_equal(buf.x_q.cpu().numpy()[:Rr], xq_tok[tok])
-            assert np.array_equal(buf.x_s.cpu().numpy()[:Rr], xs_tok[tok])
+            assert np.array_equal(R.scales_to_canonical(buf.x_s, Rr, cfg.H), xs_tok[tok])
+            w13s_all = R.scales_to_canonical(buf.w13_s, cfg.n_local * 2 * cfg.I, cfg.H).reshape(cfg.n_local, 2 * cfg.I, -1)
+            w2s_all = R.scales_to_canonical(buf.w2_s, cfg.n_local * cfg.H, cfg.I).reshape(cfg.n_local, cfg.H, -1)
+            hs_all = R.scales_to_canonical(buf.h_s, Rr, cfg.I)
             hq_gpu = buf.h_mid.view(torch.uint8).reshape(-1)[: buf.max_rows * (cfg.I // 2)].reshape(buf.max_rows, cfg.I // 2)
             for e, rows in samples:
                 w13q, w13s = omx.quantize(inp["w13"][e:e + 1])
                 w2q, w2s = omx.quantize(inp["w2"][e:e + 1])
                 assert np.array_equal(buf.w13_q[e].cpu().numpy(), omx.pack(w13q[0]))
-                assert np.array_equal(buf.w13_s[e].cpu().numpy(), w13s[0])
+                assert np.array_equal(w13s_all[e], w13s[0])
                 assert np.array_equal(buf.w2_q[e].cpu().numpy(), omx.pack(w2q[0]))
-                assert np.array_equal(buf.w2_s[e].cpu().numpy(), w2s[0])
+                assert np.array_equal(w2s_all[e], w2s[0])
                 xq = omx.unpack(xq_tok[tok[rows]])
                 hq, hs, y = offn.ffn_fp4(xq, xs_tok[tok[rows]], w13q, w13s, w2q, w2s, [0, len(rows)])
                 # stage-isolated: the oracle's down GEMM on the GPU's own intermediate codes
                 hq_g = omx.unpack(hq_gpu[torch.from_numpy(rows).cuda()].cpu().numpy())
-                hs_g = buf.h_s[torch.from_numpy(rows).cuda()].cpu().numpy()
+                hs_g = hs_all[rows]
                 flips = (hq_g != hq).mean()
                 assert flips <= 2e-3, (e, flips)
                 y_st = offn.down_fp4(hq_g, hs_g, w2q, w2s, [0, len(rows)])

@@ -153,7 +153,8 @@ def test_quantize_experts_bit_exact(R, case):
     _sync()
     for name, bits, q, s in (("w13", case.inp["w13"], b.w13_q, b.w13_s), ("w2", case.inp["w2"], b.w2_q, b.w2_s)):
         want_q, want_s = omx.quantize_packed(bits)
-        assert same(s.cpu().numpy(), want_s), name
+        got_s = R.scales_to_canonical(s, bits.shape[0] * bits.shape[1], bits.shape[2]).reshape(want_s.shape)
+        assert same(got_s, want_s), name
         assert same(q.cpu().numpy(), want_q), name
     # the weights themselves are untouched
     assert same(R.bits_from_bf16(case.w13), case.inp["w13"])
@@ -175,20 +176,20 @@ def test_quantize_rows_every_finite_pattern_and_specials(R):
     spec[6, :] = rng.integers(0, 0x80, 32)
     spec[7, 9] = 0x0080
     blocks.append(spec)
-    bits = np.concatenate(blocks).reshape(-1, 64)                 # rows of two blocks
+    bits = np.concatenate(blocks).reshape(-1, 128)                # rows of four blocks (one K-step)
     x = R.bf16_from_bits(bits)
     q, s = R.quantize_rows_fp4(x)
     _sync()
     want_q, want_s = omx.quantize_packed(bits)
-    assert same(s.cpu().numpy(), want_s)
+    assert same(R.scales_to_canonical(s, bits.shape[0], bits.shape[1]), want_s)
     assert same(q.cpu().numpy(), want_q)
     # ragged sizes of the flat kernel: 1 row, and a size that is not a multiple of its unroll
-    for rows, K in ((1, 32), (3, 96), (1031, 160)):
+    for rows, K in ((1, 128), (3, 384), (33, 128), (1031, 640)):
         bits = W.f32_to_bf16_bits(rng.standard_normal((rows, K)).astype(np.float32))
         q, s = R.quantize_rows_fp4(R.bf16_from_bits(bits))
         wq, ws = omx.quantize_packed(bits)
-        assert same(q.cpu().numpy(), wq) and same(s.cpu().numpy(), ws)
-    q, s = R.quantize_rows_fp4(torch.empty((0, 64), dtype=torch.bfloat16, device="cuda"))
+        assert same(q.cpu().numpy(), wq) and same(R.scales_to_canonical(s, rows, K), ws)
+    q, s = R.quantize_rows_fp4(torch.empty((0, 128), dtype=torch.bfloat16, device="cuda"))
     assert q.numel() == 0 and s.numel() == 0
 
 
@@ -212,7 +213,7 @@ def test_permute_bit_exact(R, case, prec):
         assert same(R.bits_from_bf16(b.x_perm)[:Rr], o["xperm"])
     else:
         assert same(b.x_q.cpu().numpy()[:Rr], omx.pack(o["xq"]))
-        assert same(b.x_s.cpu().numpy()[:Rr], o["xs"])
+        assert same(R.scales_to_canonical(b.x_s, Rr, c.H), o["xs"])
 
 
 # ---------------------------------------------------------------------------- FFN + combine
@@ -260,7 +261,7 @@ def test_ffn_fp4(R, case):
     Rr = int(o["expert_offsets"][-1])
     I = c.I
     hq = omx.unpack(b.h_mid.view(torch.uint8).reshape(-1)[: b.max_rows * (I // 2)].reshape(b.max_rows, I // 2).cpu().numpy()[:Rr])
-    hs = b.h_s.cpu().numpy()[:Rr]
+    hs = R.scales_to_canonical(b.h_s, Rr, I)
     # intermediate codes: boundary flips only
     scale_diff = (hs != o["hs"])
     code_diff = (hq != o["hq"]) & ~np.repeat(scale_diff, 32, axis=1)
@@ -300,7 +301,7 @@ def test_ffn_other_block_tiles_give_the_same_rows(R, case, tile):
         Rr = int(b.expert_offsets[-1])
         ref_y = b.y_rows[:Rr].clone()
         ref_h = b.h_mid.view(torch.int16).clone()
-        ref_hs = b.h_s.clone()
+        ref_hs = R.scales_to_canonical(b.h_s, Rr, case.cfg.I)
         try:
             set_gemm_tile(tile)
             b.h_mid.zero_()
@@ -311,7 +312,7 @@ def test_ffn_other_block_tiles_give_the_same_rows(R, case, tile):
         assert torch.equal(b.y_rows[:Rr].view(torch.int16), ref_y.view(torch.int16))
         assert torch.equal(b.h_mid.view(torch.int16).reshape(-1)[:n_h], ref_h.reshape(-1)[:n_h])
         if prec == R.FP4:
-            assert torch.equal(b.h_s[:Rr], ref_hs[:Rr])
+            assert np.array_equal(R.scales_to_canonical(b.h_s, Rr, case.cfg.I), ref_hs)
 
 
 # ---------------------------------------------------------------------------- whole layer
