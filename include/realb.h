@@ -188,7 +188,10 @@ typedef struct {
     const void* w13; const void* w2;            /* this rank's BF16 expert weights */
     int rank; int force;
     int overlap;                                /* weight encoding: 0 = on `stream`, 1 = on the context's side stream,
-                                                   2 = skipped (w13_q .. w2_s already hold this layer's encoded weights) */
+                                                   2 = skipped (w13_q .. w2_s already hold this layer's encoded weights),
+                                                   3 = speculative (realb_layer_forward only): issued on the side stream
+                                                       BEFORE routing, so that it fills the wait for the host's decision;
+                                                       unused if the decision is BF16 */
     long long max_rows;
     /* outputs / workspaces (caller-allocated) */
     int32_t* topk_ids; float* topk_w; int32_t* expert_cnt; int32_t* expert_vis;

@@ -7,16 +7,18 @@
 
 using namespace realb;
 
-extern "C" int realb_rank_forward(realb_ctx* ctx, realb_layer_io* io, int prec, void* stream) {
+// quant_in_flight: the weight encoding was already issued on the side stream (speculative mode)
+// and ev_join marks its end.
+static int rank_forward_impl(realb_ctx* ctx, realb_layer_io* io, int prec, void* stream, bool quant_in_flight) {
     REALB_REQUIRE(ctx && io, REALB_EINVAL, "NULL argument");
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     REALB_REQUIRE(prec == REALB_BF16 || prec == REALB_FP4, REALB_EINVAL, "bad precision %d", prec);
     hipStream_t s = as_stream(stream);
     int rc;
     const bool fp4 = prec == REALB_FP4;
-    const bool side = io->overlap == 1;
+    const bool side = io->overlap == 1 || quant_in_flight;
     if (fp4) REALB_REQUIRE(io->w13_q && io->w13_s && io->w2_q && io->w2_s, REALB_EINVAL, "NULL FP4 weight buffer");
-    if (fp4 && io->overlap != 2) {
+    if (fp4 && io->overlap != 2 && !quant_in_flight) {
         if (side) {
             REALB_HIP(hipEventRecord(c->ev_fork, s));
             REALB_HIP(hipStreamWaitEvent(c->side, c->ev_fork, 0));
@@ -39,18 +41,40 @@ extern "C" int realb_rank_forward(realb_ctx* ctx, realb_layer_io* io, int prec, 
         rc = realb_grouped_moe_ffn(ctx, prec, io->expert_offsets, c->n_local, io->max_rows, io->x_perm, nullptr, io->w13,
                                    nullptr, io->w2, nullptr, io->h_mid, nullptr, io->y_rows, stream);
     if (rc != REALB_OK) return rc;
-    return realb_combine(ctx, io->y_rows, io->assign_to_row, io->topk_w, io->T, io->out, stream);
+    rc = realb_combine(ctx, io->y_rows, io->assign_to_row, io->topk_w, io->T, io->out, stream);
+    if (rc != REALB_OK) return rc;
+    // a speculative encoding that was not used still has to end before the caller's stream moves on
+    if (quant_in_flight && !fp4) REALB_HIP(hipStreamWaitEvent(s, c->ev_join, 0));
+    return REALB_OK;
+}
+
+extern "C" int realb_rank_forward(realb_ctx* ctx, realb_layer_io* io, int prec, void* stream) {
+    return rank_forward_impl(ctx, io, prec, stream, false);
 }
 
 extern "C" int realb_layer_forward(realb_ctx* ctx, realb_layer_io* io, void* stream) {
     REALB_REQUIRE(ctx && io, REALB_EINVAL, "NULL argument");
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     REALB_REQUIRE(io->rank >= 0 && io->rank < c->cfg.D, REALB_EINVAL, "rank=%d outside [0,%d)", io->rank, c->cfg.D);
-    int rc = realb_route_stats(ctx, io->logits, io->is_vision, io->T, io->topk_ids, io->topk_w, io->expert_cnt, io->expert_vis,
-                               io->rank_load, io->rank_vis, stream);
+    int rc;
+    // Speculative mode: the weight encoding depends on the weights only, so it can start on the
+    // side stream before routing and fill the window in which the GPU waits for the host's
+    // precision decision.  If the decision is BF16 its output is simply not used.
+    const bool speculative = io->overlap == 3 && io->force != REALB_BF16;
+    if (speculative) {
+        REALB_REQUIRE(io->w13_q && io->w13_s && io->w2_q && io->w2_s, REALB_EINVAL, "NULL FP4 weight buffer");
+        hipStream_t s = as_stream(stream);
+        REALB_HIP(hipEventRecord(c->ev_fork, s));
+        REALB_HIP(hipStreamWaitEvent(c->side, c->ev_fork, 0));
+        rc = realb_quantize_experts_fp4(ctx, io->w13, io->w2, c->n_local, io->w13_q, io->w13_s, io->w2_q, io->w2_s, c->side);
+        if (rc != REALB_OK) return rc;
+        REALB_HIP(hipEventRecord(c->ev_join, c->side));
+    }
+    rc = realb_route_stats(ctx, io->logits, io->is_vision, io->T, io->topk_ids, io->topk_w, io->expert_cnt, io->expert_vis,
+                           io->rank_load, io->rank_vis, stream);
     if (rc != REALB_OK) return rc;
     rc = realb_select_precision(ctx, io->rank_load, io->rank_vis, io->T, io->force, io->prec_host, &io->ib_global,
                                 &io->M_after, stream);
     if (rc != REALB_OK) return rc;
-    return realb_rank_forward(ctx, io, io->prec_host[io->rank], stream);
+    return rank_forward_impl(ctx, io, io->prec_host[io->rank], stream, speculative);
 }

@@ -323,7 +323,7 @@ def test_layer_forward_matches_step_calls_and_is_deterministic(R, case, force):
     _run_path(R, case, force)
     ref = {n: getattr(b, n).clone() for n in ("out", "y_rows", "topk_ids", "assign_to_row", "expert_offsets")}
     Rr = int(ref["expert_offsets"][-1])
-    for overlap in (True, False, True):
+    for overlap in (True, False, 3, True):          # side stream, main stream, speculative (before routing)
         io = case.ctx.make_io(case.logits, case.is_vision, case.x, case.w13, case.w2, b, case.rank, force=force, overlap=overlap)
         b.out.zero_()
         prec = case.ctx.layer_forward(io)
