@@ -28,6 +28,8 @@ struct Ctx {
 };
 
 void set_error(const char* fmt, ...);
+int select_precision_pinned(Ctx* c, int T, int force, int32_t* prec_host, double* ib_global_host, double* M_after_host,
+                            hipStream_t s);
 int hip_fail(hipError_t e, const char* what);
 
 #define REALB_HIP(call)                                                        \

@@ -68,6 +68,15 @@ static void policy(const realb_config& c, const int32_t* load, const int32_t* vi
     *M_inout = M_new;
 }
 
+// Policy on the pinned host copy of the statistics that the last realb_route_stats on `stream` wrote.
+int select_precision_pinned(Ctx* c, int T, int force, int32_t* prec_host, double* ib_global_host, double* M_after_host,
+                            hipStream_t s) {
+    REALB_HIP(hipStreamSynchronize(s));
+    policy(c->cfg, c->stats_host, c->stats_host + c->cfg.D, T, force, &c->M, prec_host, ib_global_host);
+    if (M_after_host) *M_after_host = c->M;
+    return REALB_OK;
+}
+
 }  // namespace realb
 
 using namespace realb;

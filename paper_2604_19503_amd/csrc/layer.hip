@@ -73,8 +73,9 @@ extern "C" int realb_layer_forward(realb_ctx* ctx, realb_layer_io* io, void* str
     rc = realb_route_stats(ctx, io->logits, io->is_vision, io->T, io->topk_ids, io->topk_w, io->expert_cnt, io->expert_vis,
                            io->rank_load, io->rank_vis, stream);
     if (rc != REALB_OK) return rc;
-    rc = realb_select_precision(ctx, io->rank_load, io->rank_vis, io->T, io->force, io->prec_host, &io->ib_global,
-                                &io->M_after, stream);
+    REALB_REQUIRE(io->force == REALB_FORCE_NONE || io->force == REALB_BF16 || io->force == REALB_FP4, REALB_EINVAL,
+                  "bad force value %d", io->force);
+    rc = select_precision_pinned(c, io->T, io->force, io->prec_host, &io->ib_global, &io->M_after, as_stream(stream));
     if (rc != REALB_OK) return rc;
     return rank_forward_impl(ctx, io, io->prec_host[io->rank], stream, speculative);
 }

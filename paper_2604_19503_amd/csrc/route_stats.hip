@@ -92,12 +92,14 @@ __global__ void __launch_bounds__(1024) topk_hist_kernel(const float* __restrict
     for (int i = threadIdx.x; i < 2 * E; i += blockDim.x) hist_part[(size_t)blockIdx.x * 2 * E + i] = hist[i];
 }
 
-// Adds up the blocks' partial histograms and the per-rank sums (a separate launch: the kernel
+// Adds up the blocks' partial histograms and the per-rank sums (also written to the context's pinned
+// host buffer, which realb_layer_forward reads after one stream synchronisation) (a separate launch: the kernel
 // boundary makes the partials of all XCDs visible).  Thread layout: counter c = tid % CW,
 // slice = tid / CW; each slice walks its share of the partials, LDS atomics merge the slices.
 __global__ void __launch_bounds__(1024) hist_reduce_kernel(const int32_t* __restrict__ hist_part, int n_part, int E, int D,
                                                            int32_t* __restrict__ expert_cnt, int32_t* __restrict__ expert_vis,
-                                                           int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis) {
+                                                           int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis,
+                                                           int32_t* __restrict__ stats_host) {
     extern __shared__ int32_t tot[];                  // [2*E]
     const int C2 = 2 * E;
     for (int i = threadIdx.x; i < C2; i += blockDim.x) tot[i] = 0;
@@ -120,6 +122,8 @@ __global__ void __launch_bounds__(1024) hist_reduce_kernel(const int32_t* __rest
         for (int e = 0; e < n_local; ++e) { load += tot[d * n_local + e]; vis += tot[E + d * n_local + e]; }
         rank_load[d] = load;
         rank_vis[d] = vis;
+        stats_host[d] = load;                         // pinned host copy for the policy: saves two copy launches
+        stats_host[D + d] = vis;
     }
 }
 
@@ -151,7 +155,7 @@ extern "C" int realb_route_stats(realb_ctx* ctx, const float* logits, const uint
 #undef REALB_TOPK
     }
     hipLaunchKernelGGL(hist_reduce_kernel, dim3(1), dim3(1024), 2 * (size_t)E * sizeof(int32_t), s, c->hist_part, blocks, E, D,
-                       expert_cnt, expert_vis, rank_load, rank_vis);
+                       expert_cnt, expert_vis, rank_load, rank_vis, c->stats_host);
     REALB_HIP(hipGetLastError());
     return REALB_OK;
 }
