@@ -127,6 +127,67 @@ __device__ __forceinline__ TileInfo decode_tile(const GemmParams& p, int tile, i
     return TileInfo{e, seg_lo + mi * BM, seg_hi, nt * cols_per_tile};
 }
 
+// Epilogue, straight from registers.  acc[mt][t][r] belongs to activation row wm*128 + mt*32 + li
+// of the tile and to column 16*half + r of the wave's t-th 32-column tile.  rows_valid = rows of
+// this tile that exist (may exceed the tile height).
+template <bool FP4, bool GATEUP, int WN>
+__device__ __forceinline__ void epilogue(const GemmParams& p, v16f_t (&acc)[4][WN], int row0, int rows_valid, int n0,
+                                         int wm, int wn, int li, int half) {
+    if constexpr (GATEUP) {
+        constexpr int HT = WN / 2;                     // h column tiles per wave
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+            const int m = wm * 128 + mt * 32 + li;
+            const bool valid = m < rows_valid;
+            const size_t grow = (size_t)(row0 + m);
+#pragma unroll
+            for (int t = 0; t < HT; ++t) {
+                const int ctile = n0 + wn * HT * 32 + t * 32;  // first h column of the 32-column tile
+                uint32_t hb[8];                                // 16 BF16 values: columns ctile + 16*half + 0..15
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const float g0 = acc[mt][t][2 * q], u0 = acc[mt][t + HT][2 * q];
+                    const float g1 = acc[mt][t][2 * q + 1], u1 = acc[mt][t + HT][2 * q + 1];
+                    hb[q] = pack_bf16x2(g0 * u0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)),
+                                        g1 * u1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)));
+                }
+                if constexpr (FP4) {
+                    const u32x4_t v0 = {hb[0], hb[1], hb[2], hb[3]}, v1 = {hb[4], hb[5], hb[6], hb[7]};
+                    uint32_t amax = max(amax_bits8(v0), amax_bits8(v1));
+                    amax = max(amax, (uint32_t)__shfl_xor((int)amax, 32));    // the block's other 16 columns
+                    const uint32_t byte = e8m0_from_amax(amax);
+                    const float scl = scale_operand(byte);
+                    const u32x2_t codes = {encode8(v0, scl), encode8(v1, scl)};
+                    if (valid) {
+                        *reinterpret_cast<u32x2_t*>(p.out + grow * (size_t)(p.n_out >> 1) + (ctile >> 1) + half * 8) = codes;
+                        if (half == 0) p.outs[scale_byte_offset((long long)grow, ctile >> 5, p.n_out >> 7)] = (uint8_t)byte;
+                    }
+                } else if (valid) {
+                    u32x4_t* dst = reinterpret_cast<u32x4_t*>(p.out + (grow * (size_t)p.n_out + ctile + half * 16) * 2);
+                    dst[0] = u32x4_t{hb[0], hb[1], hb[2], hb[3]};
+                    dst[1] = u32x4_t{hb[4], hb[5], hb[6], hb[7]};
+                }
+            }
+        }
+    } else {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+            const int m = wm * 128 + mt * 32 + li;
+            if (m < rows_valid) {
+#pragma unroll
+                for (int t = 0; t < WN; ++t) {
+                    const int col = n0 + wn * WN * 32 + t * 32 + half * 16;
+                    u32x4_t* dst = reinterpret_cast<u32x4_t*>(p.out + ((size_t)(row0 + m) * p.n_out + col) * 2);
+                    dst[0] = u32x4_t{pack_bf16x2(acc[mt][t][0], acc[mt][t][1]), pack_bf16x2(acc[mt][t][2], acc[mt][t][3]),
+                                     pack_bf16x2(acc[mt][t][4], acc[mt][t][5]), pack_bf16x2(acc[mt][t][6], acc[mt][t][7])};
+                    dst[1] = u32x4_t{pack_bf16x2(acc[mt][t][8], acc[mt][t][9]), pack_bf16x2(acc[mt][t][10], acc[mt][t][11]),
+                                     pack_bf16x2(acc[mt][t][12], acc[mt][t][13]), pack_bf16x2(acc[mt][t][14], acc[mt][t][15])};
+                }
+            }
+        }
+    }
+}
+
 // Blocks b, b+8, b+16, .. share an XCD (and its L2), so each XCD takes a contiguous range of tiles
 // (consecutive row tiles over all column tiles).  BF16: persistent blocks, one per residency slot,
 // walk their XCD's range with a stride, and while a tile's epilogue runs the first K-step of the
@@ -308,69 +369,310 @@ __global__ void __launch_bounds__(128 * WGN, MINB) ffn_gemm_kernel(const GemmPar
             prefetch_tile(ti);
         }
 
-        // ---- epilogue, straight from registers.  acc[mt][t][r] belongs to activation row
-        //      wm*128 + mt*32 + li and to column 16*half + r of the wave's t-th 32-column tile.
-        const int rows_valid = cur.seg_hi - cur.row0;     // rows of this tile that exist (may exceed BM)
-        const int row0 = cur.row0, n0 = cur.n0;
-        if constexpr (GATEUP) {
-            constexpr int HT = WN / 2;                     // h column tiles per wave
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt) {
-                const int m = wm * 128 + mt * 32 + li;
-                const bool valid = m < rows_valid;
-                const size_t grow = (size_t)(row0 + m);
-#pragma unroll
-                for (int t = 0; t < HT; ++t) {
-                    const int ctile = n0 + wn * HT * 32 + t * 32;  // first h column of the 32-column tile
-                    uint32_t hb[8];                                // 16 BF16 values: columns ctile + 16*half + 0..15
-#pragma unroll
-                    for (int q = 0; q < 8; ++q) {
-                        const float g0 = acc[mt][t][2 * q], u0 = acc[mt][t + HT][2 * q];
-                        const float g1 = acc[mt][t][2 * q + 1], u1 = acc[mt][t + HT][2 * q + 1];
-                        hb[q] = pack_bf16x2(g0 * u0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)),
-                                            g1 * u1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)));
-                    }
-                    if constexpr (FP4) {
-                        const u32x4_t v0 = {hb[0], hb[1], hb[2], hb[3]}, v1 = {hb[4], hb[5], hb[6], hb[7]};
-                        uint32_t amax = max(amax_bits8(v0), amax_bits8(v1));
-                        amax = max(amax, (uint32_t)__shfl_xor((int)amax, 32));    // the block's other 16 columns
-                        const uint32_t byte = e8m0_from_amax(amax);
-                        const float scl = scale_operand(byte);
-                        const u32x2_t codes = {encode8(v0, scl), encode8(v1, scl)};
-                        if (valid) {
-                            *reinterpret_cast<u32x2_t*>(p.out + grow * (size_t)(p.n_out >> 1) + (ctile >> 1) + half * 8) = codes;
-                            if (half == 0) p.outs[scale_byte_offset((long long)grow, ctile >> 5, p.n_out >> 7)] = (uint8_t)byte;
-                        }
-                    } else if (valid) {
-                        u32x4_t* dst = reinterpret_cast<u32x4_t*>(p.out + (grow * (size_t)p.n_out + ctile + half * 16) * 2);
-                        dst[0] = u32x4_t{hb[0], hb[1], hb[2], hb[3]};
-                        dst[1] = u32x4_t{hb[4], hb[5], hb[6], hb[7]};
-                    }
-                }
-            }
-        } else {
-#pragma unroll
-            for (int mt = 0; mt < 4; ++mt) {
-                const int m = wm * 128 + mt * 32 + li;
-                if (m < rows_valid) {
-#pragma unroll
-                    for (int t = 0; t < WN; ++t) {
-                        const int col = n0 + wn * WN * 32 + t * 32 + half * 16;
-                        u32x4_t* dst = reinterpret_cast<u32x4_t*>(p.out + ((size_t)(row0 + m) * p.n_out + col) * 2);
-                        dst[0] = u32x4_t{pack_bf16x2(acc[mt][t][0], acc[mt][t][1]), pack_bf16x2(acc[mt][t][2], acc[mt][t][3]),
-                                         pack_bf16x2(acc[mt][t][4], acc[mt][t][5]), pack_bf16x2(acc[mt][t][6], acc[mt][t][7])};
-                        dst[1] = u32x4_t{pack_bf16x2(acc[mt][t][8], acc[mt][t][9]), pack_bf16x2(acc[mt][t][10], acc[mt][t][11]),
-                                         pack_bf16x2(acc[mt][t][12], acc[mt][t][13]), pack_bf16x2(acc[mt][t][14], acc[mt][t][15])};
-                    }
-                }
-            }
-        }
+        // ---- epilogue, straight from registers
+        epilogue<FP4, GATEUP, WN>(p, acc, cur.row0, cur.seg_hi - cur.row0, cur.n0, wm, wn, li, half);
         if (!more) break;
     }
 }
 
-// Block tile choices (selector g_tile): 2 = 256x128, 4 waves, two blocks per CU;
-// 8 = 256x256, 8 waves of 128x64, one block per CU.
+// ---------------------------------------------------------------------------------------------
+// 256 x 256 tile kernel with direct-to-LDS loads (the default where the output width allows).
+//
+// What bounds the grouped GEMM on this chip is the path from L2 into the CU, not the MFMA rate:
+// a CU takes in about one 1-KB vector-memory instruction per 18-26 cycles, and the vector L1
+// fetches whole 128-byte lines.  So this kernel
+//   - fetches 128 bytes of every operand row per K-step (a full line: 256 FP4 or 64 BF16 values,
+//     four MFMA K-slices), which halves the L2->L1 traffic of 64-byte steps;
+//   - uses a 256 x 256 block tile (8 waves of 128 x 64), the largest whose two 64-KB stages fit the
+//     160 KB of LDS, to minimise bytes fetched per MFMA;
+//   - loads with global_load_lds_dwordx4 (memory -> LDS without passing through registers): a wave
+//     instruction carries 8 rows x 128 B and lands as 1 KB of contiguous LDS.  Inside a 128-byte LDS
+//     row the eight 16-byte parts are XOR-swizzled by (row>>1)&7 (done on the global address of
+//     each lane, since the LDS side of the transfer is fixed), which makes the 32-row x 16-byte
+//     fragment reads bank-conflict free;
+//   - paces the loads between the MFMAs of the middle K-slices (a wave blocks while the memory
+//     pipeline accepts an instruction, and eight waves issuing at once stall all MFMA issue);
+//   - is persistent: a block walks its XCD's tile range, and the last K-step of a tile already
+//     fetches the first K-step of the next one, so only the register-only epilogue sits between
+//     two tiles' MFMA streams;
+//   - FP4: stages the E8M0 scales through LDS as well (global_load_lds_dword, 32 rows x 2 dwords
+//     per instruction), because one vector-memory instruction per lane-dword costs as much issue
+//     time as a 1-KB one.
+// The accumulation order along K is that of the other kernel, so results are bit-identical.
+namespace t256 {
+constexpr int KB = 128;                    // bytes of each operand row per K-step
+constexpr int REGION_W = 256 * KB;         // weight rows follow the 256 activation rows
+constexpr int STAGE = 512 * KB;            // 64 KB
+constexpr int SC_BASE = 2 * STAGE;         // FP4: scale staging, per stage [512 rows][2 dwords]
+constexpr int SC_STAGE = 512 * 8;
+constexpr int SC_W = 256 * 8;
+constexpr int TAB_BASE = SC_BASE + 2 * SC_STAGE;   // expert table, 3 x 64 ints
+constexpr int LDS_BYTES = TAB_BASE + 3 * 64 * 4;
+}  // namespace t256
+
+__device__ __forceinline__ void lds_dma16(const uint8_t* g, uint8_t* l) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                     (__attribute__((address_space(3))) void*)l, 16, 0, 0);
+}
+__device__ __forceinline__ void lds_dma4(const uint32_t* g, uint8_t* l) {
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                     (__attribute__((address_space(3))) void*)l, 4, 0, 0);
+}
+
+template <int N> struct IntC { static constexpr int value = N; };
+
+template <bool FP4, bool GATEUP>
+__global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p) {
+    using namespace t256;
+    constexpr int COLS = GATEUP ? 128 : 256;   // output columns per block
+    extern __shared__ __align__(16) uint8_t smem[];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 2, wn = wave & 3;
+    const int li = lane & 31, half = lane >> 5;
+
+    // Expert table in LDS: entry e holds expert e's row segment and the inclusive prefix of row-tile
+    // counts (entries up to 63 repeat the total), so that decoding a tile index is one LDS read per
+    // lane, a ballot and three broadcast reads -- no global memory access between tiles.
+    int* tab = reinterpret_cast<int*>(smem + TAB_BASE);    // [0,64) prefix, [64,128) segment start, [128,192) segment end
+    int total_m;
+    {
+        int off_lo = 0, off_hi = 0;
+        if (lane < p.n_local) { off_lo = p.offs[lane]; off_hi = p.offs[lane + 1]; }
+        int cum = (off_hi - off_lo + BM - 1) / BM;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int o = __shfl_up(cum, d);
+            if (lane >= d) cum += o;
+        }
+        total_m = __builtin_amdgcn_readlane(cum, 63);
+        if (wave == 0) { tab[lane] = cum; tab[64 + lane] = off_lo; tab[128 + lane] = off_hi; }
+        __syncthreads();
+    }
+    const int total = total_m * p.n_tiles_n;
+    auto decode = [&](int t) __attribute__((always_inline)) {
+        const int mi = t / p.n_tiles_n, nt = t - mi * p.n_tiles_n;
+        const int e = __builtin_amdgcn_readfirstlane(__popcll(__ballot(tab[lane] <= mi)));   // experts that end at or before row tile mi
+        const int lo = __builtin_amdgcn_readfirstlane(tab[64 + e]), hi = __builtin_amdgcn_readfirstlane(tab[128 + e]);
+        const int first = e == 0 ? 0 : __builtin_amdgcn_readfirstlane(tab[e - 1]);
+        return TileInfo{e, lo + (mi - first) * BM, hi, nt * COLS};
+    };
+    const int per_xcd = (total + 7) >> 3;
+    const int nslots = gridDim.x >> 3;
+    const int tile_hi = min(total, ((int)(blockIdx.x & 7) + 1) * per_xcd);
+    int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (tile >= tile_hi) return;
+
+    const int I_up = p.w_rows >> 1;
+    const uint32_t rowbytes = FP4 ? (uint32_t)(p.K >> 1) : (uint32_t)p.K * 2;
+    const int nks = (int)((rowbytes + KB - 1) / KB);
+    const bool tail_half = (rowbytes % KB) != 0;          // last K-step holds 64 bytes per row
+    const int kd = p.K >> 7;                              // FP4: scale dwords per row
+
+    // ---- consumer side: fragment offsets inside a stage
+    const int sw = (li >> 1) & 7;
+    const int f_off0 = li * KB + ((half ^ sw) << 4);       // slice s reads part 2s+half: offset f_off0 ^ (s << 5)
+    const int a_base = wm * 128 * KB;
+    int b_pos[2];                                         // first LDS weight position of the wave's two column tiles
+    if constexpr (GATEUP) { b_pos[0] = wn * 32; b_pos[1] = 128 + wn * 32; }
+    else { b_pos[0] = wn * 64; b_pos[1] = wn * 64 + 32; }
+
+    // ---- producer side: this wave moves activation rows and weight positions 32*wave .. 32*wave+31
+    //      (four instructions of 8 rows each) and the scale dwords of the same rows.  Addresses are a
+    //      per-tile scalar base plus a 32-bit per-lane offset.
+    const int prow = lane >> 3;                           // row inside an 8-row instruction
+    uint32_t a_voff[4], b_voff[4];                        // byte offsets from the tile's first activation / weight row
+    // 16-byte part a lane fetches in instruction j: (lane&7) ^ key, key = (R>>1)&7 = (4*(j&1) + (lane>>4)) & 7
+    auto part16 = [&](int q) __attribute__((always_inline)) { return (uint32_t)(((lane & 7) ^ ((q * 4 + (lane >> 4)) & 7)) << 4); };
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int R = (wave * 4 + j) * 8 + prow;          // ((R>>1)&7 == (4*(j&1) + (lane>>4)) & 7: the swizzle key of LDS row R)
+        const int br = (R & ~31) | w_row_of_lane(R & 31);
+        b_voff[j] = (uint32_t)w_tile_row<GATEUP, 128>(br, 0, I_up) * rowbytes + part16(j & 1);
+        a_voff[j] = 0;                                    // set per tile (row clamp)
+    }
+    const int srow = wave * 32 + (lane >> 1), swhich = lane & 1;
+    int sa_idx = 0, sb_idx = 0;                           // FP4: dword index of this lane's scale word, K-step 0
+    const uint8_t* a_tile = nullptr;                      // scalar: first activation row / weight row of the tile being fetched
+    const uint8_t* b_tile = nullptr;
+
+    TileInfo ti = decode(tile);
+    auto setup_src = [&](const TileInfo& t) __attribute__((always_inline)) {
+        const int row0 = __builtin_amdgcn_readfirstlane(t.row0), rows = __builtin_amdgcn_readfirstlane(t.seg_hi - t.row0);
+        const int e = __builtin_amdgcn_readfirstlane(t.e), n0 = __builtin_amdgcn_readfirstlane(t.n0);
+        a_tile = p.A + (size_t)row0 * rowbytes;
+        b_tile = p.W + ((size_t)e * p.w_rows + n0) * rowbytes;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int R = (wave * 4 + j) * 8 + prow;
+            a_voff[j] = part16(j & 1) + (uint32_t)min(R, rows - 1) * rowbytes;
+        }
+        if constexpr (FP4) {
+            const int gr = row0 + min(srow, rows - 1);
+            sa_idx = ((gr >> 5) * kd) * 32 + (gr & 31);
+            const int br = (srow & ~31) | w_row_of_lane(srow & 31);
+            const int wr = e * p.w_rows + w_tile_row<GATEUP, 128>(br, n0, I_up);
+            sb_idx = ((wr >> 5) * kd) * 32 + (wr & 31);
+        }
+    };
+    // One producer instruction of K-step k into stage `dstg`: op 0/1 = scales (FP4), 2..5 = activations, 6..9 = weights.
+    auto issue = [&](int op, int k, int dstg) __attribute__((always_inline)) {
+        if (op < 2) {
+            if constexpr (FP4) {
+                const int ko = min(2 * k + swhich, kd - 1) * 32;
+                uint8_t* l = smem + SC_BASE + dstg * SC_STAGE + wave * 256;
+                if (op == 0) lds_dma4(reinterpret_cast<const uint32_t*>(p.As) + (uint32_t)(sa_idx + ko), l);
+                else lds_dma4(reinterpret_cast<const uint32_t*>(p.Ws) + (uint32_t)(sb_idx + ko), l + SC_W);
+            }
+        } else {
+            const int j = (op - 2) & 3;
+            const bool halfstep = tail_half && k == nks - 1;
+            // half step: lanes of parts 4..7 fetch parts 0..3 again (the row has only 64 bytes left)
+            const uint32_t koff = (uint32_t)(k * KB) - (halfstep ? (uint32_t)(((lane << 4) ^ ((j & 1) << 6)) & 64) : 0u);
+            uint8_t* l = smem + dstg * STAGE + (wave * 4 + j) * 1024;
+            if (op < 6) lds_dma16(a_tile + (a_voff[j] + koff), l);
+            else lds_dma16(b_tile + (b_voff[j] + koff), l + REGION_W);
+        }
+    };
+
+    setup_src(ti);
+#pragma unroll
+    for (int op = 0; op < 10; ++op) issue(op, 0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    // One flat loop over the (tile, K-step) pairs of this block, with a single copy of the K-step code:
+    // the steps of a tile follow each other without a seam, and a tile's last step already fetches the
+    // next tile's first one.
+    int stg = 0, ks = 0;
+    v16f_t acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+    int cur_row0 = ti.row0, cur_rows = ti.seg_hi - ti.row0, cur_n0 = ti.n0;
+    bool more = false;
+    while (true) {
+        const bool last = ks == nks - 1;
+        int nk = ks + 1;                                  // K-step the producer fetches during this one
+        if (last) {
+            more = tile + nslots < tile_hi;
+            if (more) {
+                tile += nslots;
+                ti = decode(tile);
+                setup_src(ti);
+            }
+            nk = 0;                                       // next tile's first step (no next tile: a harmless refetch)
+        }
+        const bool full = !(last && tail_half);           // all four K-slices present
+        {
+            const uint8_t* st = smem + stg * STAGE;
+            const int dstg = stg ^ 1;
+            int sa[4][2], sb[2][2];
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) sa[mt][0] = sa[mt][1] = 0;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) sb[t][0] = sb[t][1] = 0;
+            if constexpr (FP4) {
+                const uint8_t* sc = smem + SC_BASE + stg * SC_STAGE;
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt) {
+                    const u32x2_t v = *reinterpret_cast<const u32x2_t*>(sc + (wm * 128 + mt * 32 + li) * 8);
+                    sa[mt][0] = (int)(v.x >> (half * 8));
+                    sa[mt][1] = (int)(v.y >> (half * 8));
+                }
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const u32x2_t v = *reinterpret_cast<const u32x2_t*>(sc + SC_W + (b_pos[t] + li) * 8);
+                    sb[t][0] = (int)(v.x >> (half * 8));
+                    sb[t][1] = (int)(v.y >> (half * 8));
+                }
+            }
+            // Fragments of slice s+1 are read while slice s multiplies; the producer's ten instructions go
+            // between the MFMAs, from the second slice on so that the MFMAs start right after the barrier.
+            u32x4_t fa[2][4], fb[2][2];
+            auto read_frags = [&](int s) __attribute__((always_inline)) {
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt) fa[s & 1][mt] = *reinterpret_cast<const u32x4_t*>(st + a_base + mt * 32 * KB + (f_off0 ^ (s << 5)));
+#pragma unroll
+                for (int t = 0; t < 2; ++t) fb[s & 1][t] = *reinterpret_cast<const u32x4_t*>(st + REGION_W + b_pos[t] * KB + (f_off0 ^ (s << 5)));
+            };
+            // MFMAs of slice s; after the MFMAs of row tile mt, producer instruction op0 + mt (op0 < 0: none)
+            auto slice = [&](int s, int op0) __attribute__((always_inline)) {
+#pragma unroll
+                for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        if (s & 1) mma<FP4, 2>(acc[mt][t], fb[s & 1][t], fa[s & 1][mt], sb[t][s >> 1], sa[mt][s >> 1]);
+                        else mma<FP4, 0>(acc[mt][t], fb[s & 1][t], fa[s & 1][mt], sb[t][s >> 1], sa[mt][s >> 1]);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (op0 >= 0) issue(op0 + mt, nk, dstg);
+                    else if (op0 == -2 && (mt & 1)) issue(mt >> 1, nk, dstg);     // the two scale instructions
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            };
+            read_frags(0);
+            read_frags(1);
+            __builtin_amdgcn_sched_barrier(0);
+            slice(0, FP4 ? -2 : -1);
+            read_frags(2);                                // (half step: reads stale bytes that are never multiplied)
+            __builtin_amdgcn_sched_barrier(0);
+            slice(1, 2);
+            if (full) {
+                read_frags(3);
+                __builtin_amdgcn_sched_barrier(0);
+                slice(2, 6);
+                slice(3, -1);
+            } else {
+#pragma unroll
+                for (int op = 6; op < 10; ++op) issue(op, nk, dstg);
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            stg ^= 1;
+        }
+        ++ks;
+        if (last) {
+            epilogue<FP4, GATEUP, 2>(p, acc, cur_row0, cur_rows, cur_n0, wm, wn, li, half);
+            if (!more) break;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+            cur_row0 = ti.row0; cur_rows = ti.seg_hi - ti.row0; cur_n0 = ti.n0;
+            ks = 0;
+        }
+    }
+}
+
+template <bool FP4, bool GATEUP>
+static int launch_gemm256(GemmParams p, long long max_rows, int num_cus, hipStream_t s) {
+    p.n_tiles_n = p.n_out / (GATEUP ? 128 : 256);
+    const size_t lds = t256::LDS_BYTES;
+    static bool attr_done = false;
+    if (!attr_done) {
+        REALB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_gemm256_kernel<FP4, GATEUP>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+        attr_done = true;
+    }
+    const long long m_tiles_max = (max_rows + BM - 1) / BM + p.n_local;
+    const long long total_max = m_tiles_max * p.n_tiles_n;
+    const long long slots = 8ll * (((long long)num_cus + 7) / 8);          // one persistent block per CU, multiple of 8 (XCDs)
+    const long long grid = total_max < slots ? 8 * ((total_max + 7) / 8) : slots;
+    hipLaunchKernelGGL((ffn_gemm256_kernel<FP4, GATEUP>), dim3((unsigned)grid), dim3(512), lds, s, p);
+    REALB_HIP(hipGetLastError());
+    return REALB_OK;
+}
+
+// Block tile choices (selector g_tile): 16 = the direct-to-LDS 256x256 kernel above (automatic choice
+// where the output width is a multiple of its tile); the register-staged kernel with 64-byte K-steps
+// as 2 = 256x128, 4 waves, two blocks per CU, or 8 = 256x256, 8 waves of 128x64, one block per CU.
 template <bool FP4, bool GATEUP, int WN, int WGN, int MINB>
 static int launch_gemm_geo(GemmParams p, long long max_rows, int num_cus, hipStream_t s) {
     using G = Geo<WN, WGN>;
@@ -395,13 +697,14 @@ static int launch_gemm_geo(GemmParams p, long long max_rows, int num_cus, hipStr
     return REALB_OK;
 }
 
-static int g_tile = 0;    // 0 = automatic; 2 or 8 forces a geometry (set through realb_set_gemm_tile)
+static int g_tile = 0;    // 0 = automatic; 2, 8 or 16 forces a kernel (set through realb_set_gemm_tile)
 
 template <bool FP4, bool GATEUP>
 static int launch_gemm(const GemmParams& p, long long max_rows, int num_cus, hipStream_t s) {
     const int unit256 = GATEUP ? 128 : 256;             // output columns per block of the 256-wide tile
     const bool can256 = p.n_out % unit256 == 0;
-    const int sel = !can256 ? 2 : (g_tile == 0 ? (FP4 ? 2 : 8) : g_tile);   // measured: BF16 prefers the 256-wide tile
+    const int sel = !can256 ? 2 : (g_tile == 0 ? 16 : g_tile);
+    if (sel == 16) return launch_gemm256<FP4, GATEUP>(p, max_rows, num_cus, s);
     if (sel == 8) return launch_gemm_geo<FP4, GATEUP, 2, 4, 1>(p, max_rows, num_cus, s);
     return launch_gemm_geo<FP4, GATEUP, 2, 2, 2>(p, max_rows, num_cus, s);
 }
@@ -411,7 +714,7 @@ static int launch_gemm(const GemmParams& p, long long max_rows, int num_cus, hip
 using namespace realb;
 
 extern "C" int realb_set_gemm_tile(int wn) {
-    REALB_REQUIRE(wn == 0 || wn == 2 || wn == 8, REALB_EINVAL, "tile selector must be 0, 2 or 8");
+    REALB_REQUIRE(wn == 0 || wn == 2 || wn == 8 || wn == 16, REALB_EINVAL, "tile selector must be 0, 2, 8 or 16");
     g_tile = wn;
     return REALB_OK;
 }

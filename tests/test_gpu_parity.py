@@ -288,10 +288,11 @@ def test_ffn_fp4(R, case):
     assert rel_fro(out, o["out"]) <= 2 * FP4_TOL
 
 
-@pytest.mark.parametrize("tile", [8])
+@pytest.mark.parametrize("tile", [8, 16])
 def test_ffn_other_block_tiles_give_the_same_rows(R, case, tile):
-    """The 256x256 block tile (8 waves) produces bit-identical outputs to the default
-    tile: the per-element FP32 accumulation order along K does not depend on the tile."""
+    """The other GEMM kernels / block tiles (8 = register-staged 256x256, 16 = direct-to-LDS 256x256)
+    produce bit-identical outputs to the 256x128 tile: the per-element FP32 accumulation order along
+    K does not depend on the tile."""
     from paper_2604_19503_amd.binding import set_gemm_tile
     b = case.buf
     for prec in (R.BF16, R.FP4):
