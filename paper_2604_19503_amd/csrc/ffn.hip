@@ -544,7 +544,10 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
 
     // One flat loop over the (tile, K-step) pairs of this block, with a single copy of the K-step code:
     // the steps of a tile follow each other without a seam, and a tile's last step already fetches the
-    // next tile's first one.
+    // next tile's first one.  Inside a step the block barrier sits after the third K-slice: by then
+    // every wave holds its fourth slice in registers, so the stage is free for the producer, and the
+    // first fragments and the scales of the NEXT step are read behind the barrier while the fourth
+    // slice multiplies -- no LDS latency is exposed at the start of a step.
     int stg = 0, ks = 0;
     v16f_t acc[4][2];
 #pragma unroll
@@ -555,6 +558,39 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     int cur_row0 = ti.row0, cur_rows = ti.seg_hi - ti.row0, cur_n0 = ti.n0;
     bool more = false;
+
+    u32x4_t fa[2][4], fb[2][2];                           // fragment double buffer (slice parity)
+    int sa[4][2], sb[2][2];                               // FP4: scale words of the step, [.][0] slices 0-1, [.][1] slices 2-3
+    auto read_frags = [&](int s, int slot, const uint8_t* st) __attribute__((always_inline)) {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) fa[slot][mt] = *reinterpret_cast<const u32x4_t*>(st + a_base + mt * 32 * KB + (f_off0 ^ (s << 5)));
+#pragma unroll
+        for (int t = 0; t < 2; ++t) fb[slot][t] = *reinterpret_cast<const u32x4_t*>(st + REGION_W + b_pos[t] * KB + (f_off0 ^ (s << 5)));
+    };
+    auto read_scales = [&](int (&xa)[4][2], int (&xb)[2][2], int stage) __attribute__((always_inline)) {
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) xa[mt][0] = xa[mt][1] = 0;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) xb[t][0] = xb[t][1] = 0;
+        if constexpr (FP4) {
+            const uint8_t* sc = smem + SC_BASE + stage * SC_STAGE;
+#pragma unroll
+            for (int mt = 0; mt < 4; ++mt) {
+                const u32x2_t v = *reinterpret_cast<const u32x2_t*>(sc + (wm * 128 + mt * 32 + li) * 8);
+                xa[mt][0] = (int)(v.x >> (half * 8));
+                xa[mt][1] = (int)(v.y >> (half * 8));
+            }
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const u32x2_t v = *reinterpret_cast<const u32x2_t*>(sc + SC_W + (b_pos[t] + li) * 8);
+                xb[t][0] = (int)(v.x >> (half * 8));
+                xb[t][1] = (int)(v.y >> (half * 8));
+            }
+        }
+    };
+    read_scales(sa, sb, 0);
+    read_frags(0, 0, smem);
+
     while (true) {
         const bool last = ks == nks - 1;
         int nk = ks + 1;                                  // K-step the producer fetches during this one
@@ -568,73 +604,53 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
             nk = 0;                                       // next tile's first step (no next tile: a harmless refetch)
         }
         const bool full = !(last && tail_half);           // all four K-slices present
-        {
-            const uint8_t* st = smem + stg * STAGE;
-            const int dstg = stg ^ 1;
-            int sa[4][2], sb[2][2];
+        const uint8_t* st = smem + stg * STAGE;
+        const int dstg = stg ^ 1;
+
+        // MFMAs of slice s out of fragment slot s&1; PRODUCE: the producer's ten instructions follow the
+        // MFMAs of the first two slices (scales first)
+        auto slice = [&](int s, bool produce, const int (&xa)[4][2], const int (&xb)[2][2]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) sa[mt][0] = sa[mt][1] = 0;
-#pragma unroll
-            for (int t = 0; t < 2; ++t) sb[t][0] = sb[t][1] = 0;
-            if constexpr (FP4) {
-                const uint8_t* sc = smem + SC_BASE + stg * SC_STAGE;
-#pragma unroll
-                for (int mt = 0; mt < 4; ++mt) {
-                    const u32x2_t v = *reinterpret_cast<const u32x2_t*>(sc + (wm * 128 + mt * 32 + li) * 8);
-                    sa[mt][0] = (int)(v.x >> (half * 8));
-                    sa[mt][1] = (int)(v.y >> (half * 8));
-                }
+            for (int mt = 0; mt < 4; ++mt) {
 #pragma unroll
                 for (int t = 0; t < 2; ++t) {
-                    const u32x2_t v = *reinterpret_cast<const u32x2_t*>(sc + SC_W + (b_pos[t] + li) * 8);
-                    sb[t][0] = (int)(v.x >> (half * 8));
-                    sb[t][1] = (int)(v.y >> (half * 8));
+                    if (s & 1) mma<FP4, 2>(acc[mt][t], fb[s & 1][t], fa[s & 1][mt], xb[t][s >> 1], xa[mt][s >> 1]);
+                    else mma<FP4, 0>(acc[mt][t], fb[s & 1][t], fa[s & 1][mt], xb[t][s >> 1], xa[mt][s >> 1]);
                 }
-            }
-            // Fragments of slice s+1 are read while slice s multiplies; the producer's ten instructions go
-            // between the MFMAs, from the second slice on so that the MFMAs start right after the barrier.
-            u32x4_t fa[2][4], fb[2][2];
-            auto read_frags = [&](int s) __attribute__((always_inline)) {
-#pragma unroll
-                for (int mt = 0; mt < 4; ++mt) fa[s & 1][mt] = *reinterpret_cast<const u32x4_t*>(st + a_base + mt * 32 * KB + (f_off0 ^ (s << 5)));
-#pragma unroll
-                for (int t = 0; t < 2; ++t) fb[s & 1][t] = *reinterpret_cast<const u32x4_t*>(st + REGION_W + b_pos[t] * KB + (f_off0 ^ (s << 5)));
-            };
-            // MFMAs of slice s; after the MFMAs of row tile mt, producer instruction op0 + mt (op0 < 0: none)
-            auto slice = [&](int s, int op0) __attribute__((always_inline)) {
-#pragma unroll
-                for (int mt = 0; mt < 4; ++mt) {
-#pragma unroll
-                    for (int t = 0; t < 2; ++t) {
-                        if (s & 1) mma<FP4, 2>(acc[mt][t], fb[s & 1][t], fa[s & 1][mt], sb[t][s >> 1], sa[mt][s >> 1]);
-                        else mma<FP4, 0>(acc[mt][t], fb[s & 1][t], fa[s & 1][mt], sb[t][s >> 1], sa[mt][s >> 1]);
-                    }
+                if (produce) {
                     __builtin_amdgcn_sched_barrier(0);
-                    if (op0 >= 0) issue(op0 + mt, nk, dstg);
-                    else if (op0 == -2 && (mt & 1)) issue(mt >> 1, nk, dstg);     // the two scale instructions
+                    if (FP4 && s == 0 && mt < 2) issue(mt, nk, dstg);
+                    issue(2 + s * 4 + mt, nk, dstg);
                     __builtin_amdgcn_sched_barrier(0);
                 }
-            };
-            read_frags(0);
-            read_frags(1);
-            __builtin_amdgcn_sched_barrier(0);
-            slice(0, FP4 ? -2 : -1);
-            read_frags(2);                                // (half step: reads stale bytes that are never multiplied)
-            __builtin_amdgcn_sched_barrier(0);
-            slice(1, 2);
-            if (full) {
-                read_frags(3);
-                __builtin_amdgcn_sched_barrier(0);
-                slice(2, 6);
-                slice(3, -1);
-            } else {
-#pragma unroll
-                for (int op = 6; op < 10; ++op) issue(op, nk, dstg);
             }
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            stg ^= 1;
+        };
+        read_frags(1, 1, st);
+        __builtin_amdgcn_sched_barrier(0);
+        slice(0, true, sa, sb);
+        read_frags(2, 0, st);                             // (half step: stale bytes that are never multiplied)
+        __builtin_amdgcn_sched_barrier(0);
+        slice(1, true, sa, sb);
+        if (full) {
+            read_frags(3, 1, st);
+            __builtin_amdgcn_sched_barrier(0);
+            slice(2, false, sa, sb);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        stg ^= 1;
+        int na[4][2], nb[2][2];
+        read_scales(na, nb, stg);
+        read_frags(0, 0, smem + stg * STAGE);
+        __builtin_amdgcn_sched_barrier(0);
+        if (full) slice(3, false, sa, sb);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) { sa[mt][0] = na[mt][0]; sa[mt][1] = na[mt][1]; }
+#pragma unroll
+        for (int t = 0; t < 2; ++t) { sb[t][0] = nb[t][0]; sb[t][1] = nb[t][1]; }
+
         ++ks;
         if (last) {
             epilogue<FP4, GATEUP, 2>(p, acc, cur_row0, cur_rows, cur_n0, wm, wn, li, half);
