@@ -482,16 +482,19 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
     //      (four instructions of 8 rows each) and the scale dwords of the same rows.  Addresses are a
     //      per-tile scalar base plus a 32-bit per-lane offset.
     const int prow = lane >> 3;                           // row inside an 8-row instruction
-    uint32_t a_voff[4], b_voff[4];                        // byte offsets from the tile's first activation / weight row
     // 16-byte part a lane fetches in instruction j: (lane&7) ^ key, key = (R>>1)&7 = (4*(j&1) + (lane>>4)) & 7
+    // for LDS row R = 32*wave + 8*j + prow of the instruction.
     auto part16 = [&](int q) __attribute__((always_inline)) { return (uint32_t)(((lane & 7) ^ ((q * 4 + (lane >> 4)) & 7)) << 4); };
+    // Weights: LDS position R holds weight-tile row (R & ~31) | w_row_of_lane(R & 31), which for
+    // R & 31 = 8*j + prow is 16*((prow>>2)&1) + 4*j + (prow&3): instruction j is 4*j rows below
+    // instruction 0, a scalar offset.  Per lane only the two part offsets differ (by parity of j).
+    uint32_t b_voff[2];
+    {
+        const int br0 = wave * 32 + (((prow >> 2) & 1) << 4) + (prow & 3);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int R = (wave * 4 + j) * 8 + prow;          // ((R>>1)&7 == (4*(j&1) + (lane>>4)) & 7: the swizzle key of LDS row R)
-        const int br = (R & ~31) | w_row_of_lane(R & 31);
-        b_voff[j] = (uint32_t)w_tile_row<GATEUP, 128>(br, 0, I_up) * rowbytes + part16(j & 1);
-        a_voff[j] = 0;                                    // set per tile (row clamp)
+        for (int q = 0; q < 2; ++q) b_voff[q] = (uint32_t)w_tile_row<GATEUP, 128>(br0, 0, I_up) * rowbytes + part16(q);
     }
+    int a_last = 0;                                       // scalar: last existing row of the tile being fetched
     const int srow = wave * 32 + (lane >> 1), swhich = lane & 1;
     int sa_idx = 0, sb_idx = 0;                           // FP4: dword index of this lane's scale word, K-step 0
     const uint8_t* a_tile = nullptr;                      // scalar: first activation row / weight row of the tile being fetched
@@ -503,11 +506,7 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
         const int e = __builtin_amdgcn_readfirstlane(t.e), n0 = __builtin_amdgcn_readfirstlane(t.n0);
         a_tile = p.A + (size_t)row0 * rowbytes;
         b_tile = p.W + ((size_t)e * p.w_rows + n0) * rowbytes;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int R = (wave * 4 + j) * 8 + prow;
-            a_voff[j] = part16(j & 1) + (uint32_t)min(R, rows - 1) * rowbytes;
-        }
+        a_last = rows - 1;
         if constexpr (FP4) {
             const int gr = row0 + min(srow, rows - 1);
             sa_idx = ((gr >> 5) * kd) * 32 + (gr & 31);
@@ -531,23 +530,45 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
             // half step: lanes of parts 4..7 fetch parts 0..3 again (the row has only 64 bytes left)
             const uint32_t koff = (uint32_t)(k * KB) - (halfstep ? (uint32_t)(((lane << 4) ^ ((j & 1) << 6)) & 64) : 0u);
             uint8_t* l = smem + dstg * STAGE + (wave * 4 + j) * 1024;
-            if (op < 6) lds_dma16(a_tile + (a_voff[j] + koff), l);
-            else lds_dma16(b_tile + (b_voff[j] + koff), l + REGION_W);
+            if (op < 6) {
+                const uint32_t v = (uint32_t)min(wave * 32 + j * 8 + prow, a_last) * rowbytes + part16(j & 1);   // rows past the segment: its last row again
+                lds_dma16(a_tile + (v + koff), l);
+            } else {
+                lds_dma16(b_tile + (size_t)(j * 4) * rowbytes + (b_voff[j & 1] + koff), l + REGION_W);
+            }
         }
     };
 
+    // ---- producer position: the K-step it fetches next (pk of tile ptile).  Past the block's last tile
+    //      it keeps refetching that tile's steps, which nobody reads.
+    int ptile = tile, pk = 0;
+    auto advance = [&]() __attribute__((always_inline)) {
+        if (++pk == nks) {
+            pk = 0;
+            if (ptile + nslots < tile_hi) {
+                ptile += nslots;
+                setup_src(decode(ptile));
+            }
+        }
+    };
     setup_src(ti);
 #pragma unroll
     for (int op = 0; op < 10; ++op) issue(op, 0, 0);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    advance();
+#pragma unroll
+    for (int op = 2; op < 6; ++op) issue(op, pk, 1);      // first half of the second step (see below)
 
     // One flat loop over the (tile, K-step) pairs of this block, with a single copy of the K-step code:
-    // the steps of a tile follow each other without a seam, and a tile's last step already fetches the
-    // next tile's first one.  Inside a step the block barrier sits after the third K-slice: by then
-    // every wave holds its fourth slice in registers, so the stage is free for the producer, and the
-    // first fragments and the scales of the NEXT step are read behind the barrier while the fourth
-    // slice multiplies -- no LDS latency is exposed at the start of a step.
+    // the steps of a tile follow each other without a seam, and the producer runs ahead across tile
+    // boundaries.  Inside a step the block barrier sits after the third K-slice: by then every wave
+    // holds its fourth slice in registers, so the stage is free, and behind the barrier
+    //   - the first fragments and the scales of the NEXT step are read while the fourth slice
+    //     multiplies (no LDS latency is exposed at the start of a step), and
+    //   - the producer starts on the step AFTER the next one: its activation rows go out between the
+    //     MFMAs of the fourth slice, its weight rows and scales between those of the next step's first
+    //     slice, so every transfer has a whole step to land before the barrier that publishes it.
     int stg = 0, ks = 0;
     v16f_t acc[4][2];
 #pragma unroll
@@ -557,7 +578,6 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
     int cur_row0 = ti.row0, cur_rows = ti.seg_hi - ti.row0, cur_n0 = ti.n0;
-    bool more = false;
 
     u32x4_t fa[2][4], fb[2][2];                           // fragment double buffer (slice parity)
     int sa[4][2], sb[2][2];                               // FP4: scale words of the step, [.][0] slices 0-1, [.][1] slices 2-3
@@ -593,58 +613,56 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
 
     while (true) {
         const bool last = ks == nks - 1;
-        int nk = ks + 1;                                  // K-step the producer fetches during this one
-        if (last) {
-            more = tile + nslots < tile_hi;
-            if (more) {
-                tile += nslots;
-                ti = decode(tile);
-                setup_src(ti);
-            }
-            nk = 0;                                       // next tile's first step (no next tile: a harmless refetch)
-        }
         const bool full = !(last && tail_half);           // all four K-slices present
         const uint8_t* st = smem + stg * STAGE;
-        const int dstg = stg ^ 1;
 
-        // MFMAs of slice s out of fragment slot s&1; PRODUCE: the producer's ten instructions follow the
-        // MFMAs of the first two slices (scales first)
-        auto slice = [&](int s, bool produce, const int (&xa)[4][2], const int (&xb)[2][2]) __attribute__((always_inline)) {
+        // MFMAs of slice s out of fragment slot s&1.  PRODUCE 1: after each row tile's MFMAs one weight
+        // transfer (and the two scale transfers) of producer step pk into the other stage; PRODUCE 2:
+        // one activation transfer of the producer's new step into the stage just released.
+        auto slice = [&](int s, int produce, bool multiply, const int (&xa)[4][2], const int (&xb)[2][2]) __attribute__((always_inline)) {
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt) {
+                if (multiply) {
 #pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    if (s & 1) mma<FP4, 2>(acc[mt][t], fb[s & 1][t], fa[s & 1][mt], xb[t][s >> 1], xa[mt][s >> 1]);
-                    else mma<FP4, 0>(acc[mt][t], fb[s & 1][t], fa[s & 1][mt], xb[t][s >> 1], xa[mt][s >> 1]);
+                    for (int t = 0; t < 2; ++t) {
+                        if (s & 1) mma<FP4, 2>(acc[mt][t], fb[s & 1][t], fa[s & 1][mt], xb[t][s >> 1], xa[mt][s >> 1]);
+                        else mma<FP4, 0>(acc[mt][t], fb[s & 1][t], fa[s & 1][mt], xb[t][s >> 1], xa[mt][s >> 1]);
+                    }
                 }
                 if (produce) {
                     __builtin_amdgcn_sched_barrier(0);
-                    if (FP4 && s == 0 && mt < 2) issue(mt, nk, dstg);
-                    issue(2 + s * 4 + mt, nk, dstg);
+                    if (produce == 1) {
+                        if (FP4 && mt < 2) issue(mt, pk, stg ^ 1);
+                        issue(6 + mt, pk, stg ^ 1);
+                    } else {
+                        issue(2 + mt, pk, stg ^ 1);       // (stg already flipped: the stage this step has just left)
+                    }
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
         };
         read_frags(1, 1, st);
         __builtin_amdgcn_sched_barrier(0);
-        slice(0, true, sa, sb);
+        slice(0, 1, true, sa, sb);
         read_frags(2, 0, st);                             // (half step: stale bytes that are never multiplied)
         __builtin_amdgcn_sched_barrier(0);
-        slice(1, true, sa, sb);
+        slice(1, 0, true, sa, sb);
         if (full) {
             read_frags(3, 1, st);
             __builtin_amdgcn_sched_barrier(0);
-            slice(2, false, sa, sb);
+            slice(2, 0, true, sa, sb);
         }
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         stg ^= 1;
+        advance();
+        __builtin_amdgcn_sched_barrier(0);
         int na[4][2], nb[2][2];
         read_scales(na, nb, stg);
         read_frags(0, 0, smem + stg * STAGE);
         __builtin_amdgcn_sched_barrier(0);
-        if (full) slice(3, false, sa, sb);
+        slice(3, 2, full, sa, sb);                        // (half step: the producer's transfers only)
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) { sa[mt][0] = na[mt][0]; sa[mt][1] = na[mt][1]; }
@@ -654,17 +672,20 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
         ++ks;
         if (last) {
             epilogue<FP4, GATEUP, 2>(p, acc, cur_row0, cur_rows, cur_n0, wm, wn, li, half);
-            if (!more) break;
+            tile += nslots;
+            if (tile >= tile_hi) break;
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int j = 0; j < 2; ++j)
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+            ti = decode(tile);
             cur_row0 = ti.row0; cur_rows = ti.seg_hi - ti.row0; cur_n0 = ti.n0;
             ks = 0;
         }
     }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // no transfer may still be writing this block's LDS when it ends
 }
 
 template <bool FP4, bool GATEUP>
