@@ -587,29 +587,31 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
 #pragma unroll
         for (int t = 0; t < 2; ++t) fb[slot][t] = *reinterpret_cast<const u32x4_t*>(st + REGION_W + b_pos[t] * KB + (f_off0 ^ (s << 5)));
     };
-    auto read_scales = [&](int (&xa)[4][2], int (&xb)[2][2], int stage) __attribute__((always_inline)) {
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) xa[mt][0] = xa[mt][1] = 0;
-#pragma unroll
-        for (int t = 0; t < 2; ++t) xb[t][0] = xb[t][1] = 0;
+    u32x2_t ra[4], rb[2];                                 // FP4: raw scale words as read from LDS
+    auto read_scales = [&](int stage) __attribute__((always_inline)) {
         if constexpr (FP4) {
             const uint8_t* sc = smem + SC_BASE + stage * SC_STAGE;
 #pragma unroll
-            for (int mt = 0; mt < 4; ++mt) {
-                const u32x2_t v = *reinterpret_cast<const u32x2_t*>(sc + (wm * 128 + mt * 32 + li) * 8);
-                xa[mt][0] = (int)(v.x >> (half * 8));
-                xa[mt][1] = (int)(v.y >> (half * 8));
-            }
+            for (int mt = 0; mt < 4; ++mt) ra[mt] = *reinterpret_cast<const u32x2_t*>(sc + (wm * 128 + mt * 32 + li) * 8);
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const u32x2_t v = *reinterpret_cast<const u32x2_t*>(sc + SC_W + (b_pos[t] + li) * 8);
-                xb[t][0] = (int)(v.x >> (half * 8));
-                xb[t][1] = (int)(v.y >> (half * 8));
-            }
+            for (int t = 0; t < 2; ++t) rb[t] = *reinterpret_cast<const u32x2_t*>(sc + SC_W + (b_pos[t] + li) * 8);
         }
     };
-    read_scales(sa, sb, 0);
+    auto take_scales = [&]() __attribute__((always_inline)) {     // this lane's byte pair of each word (op_sel picks the byte)
+#pragma unroll
+        for (int mt = 0; mt < 4; ++mt) {
+            sa[mt][0] = FP4 ? (int)(ra[mt].x >> (half * 8)) : 0;
+            sa[mt][1] = FP4 ? (int)(ra[mt].y >> (half * 8)) : 0;
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            sb[t][0] = FP4 ? (int)(rb[t].x >> (half * 8)) : 0;
+            sb[t][1] = FP4 ? (int)(rb[t].y >> (half * 8)) : 0;
+        }
+    };
+    read_scales(0);
     read_frags(0, 0, smem);
+    take_scales();
 
     while (true) {
         const bool last = ks == nks - 1;
@@ -619,55 +621,46 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
         // MFMAs of slice s out of fragment slot s&1.  PRODUCE 1: after each row tile's MFMAs one weight
         // transfer (and the two scale transfers) of producer step pk into the other stage; PRODUCE 2:
         // one activation transfer of the producer's new step into the stage just released.
-        auto slice = [&](int s, int produce, bool multiply, const int (&xa)[4][2], const int (&xb)[2][2]) __attribute__((always_inline)) {
+        // Slice s multiplies out of fragment slot s&1.  The fragments of the following slice (next = s+1,
+        // or next = 4: the first slice of the next step, with its scales, out of the stage that has just
+        // been published) are requested right after the first row tile's MFMAs: the other slot is free by
+        // then, and the wait in front of this slice's first MFMA does not cover the new request.
+        auto slice = [&](int s, int produce, bool multiply, int next) __attribute__((always_inline)) {
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt) {
                 if (multiply) {
 #pragma unroll
                     for (int t = 0; t < 2; ++t) {
-                        if (s & 1) mma<FP4, 2>(acc[mt][t], fb[s & 1][t], fa[s & 1][mt], xb[t][s >> 1], xa[mt][s >> 1]);
-                        else mma<FP4, 0>(acc[mt][t], fb[s & 1][t], fa[s & 1][mt], xb[t][s >> 1], xa[mt][s >> 1]);
+                        if (s & 1) mma<FP4, 2>(acc[mt][t], fb[s & 1][t], fa[s & 1][mt], sb[t][s >> 1], sa[mt][s >> 1]);
+                        else mma<FP4, 0>(acc[mt][t], fb[s & 1][t], fa[s & 1][mt], sb[t][s >> 1], sa[mt][s >> 1]);
                     }
                 }
-                if (produce) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (produce == 1) {
-                        if (FP4 && mt < 2) issue(mt, pk, stg ^ 1);
-                        issue(6 + mt, pk, stg ^ 1);
-                    } else {
-                        issue(2 + mt, pk, stg ^ 1);       // (stg already flipped: the stage this step has just left)
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (mt == 0 && next >= 0) {
+                    if (next < 4) read_frags(next, next & 1, st);
+                    else { read_scales(stg); read_frags(0, 0, smem + stg * STAGE); }
                 }
+                if (produce == 1) {
+                    if (FP4 && mt < 2) issue(mt, pk, stg ^ 1);
+                    issue(6 + mt, pk, stg ^ 1);
+                } else if (produce == 2) {
+                    issue(2 + mt, pk, stg ^ 1);           // (stg already flipped: the stage this step has just left)
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
         };
-        read_frags(1, 1, st);
-        __builtin_amdgcn_sched_barrier(0);
-        slice(0, 1, true, sa, sb);
-        read_frags(2, 0, st);                             // (half step: stale bytes that are never multiplied)
-        __builtin_amdgcn_sched_barrier(0);
-        slice(1, 0, true, sa, sb);
-        if (full) {
-            read_frags(3, 1, st);
-            __builtin_amdgcn_sched_barrier(0);
-            slice(2, 0, true, sa, sb);
-        }
+        slice(0, 1, true, 1);
+        slice(1, 0, true, 2);                             // (half step: slice 2 holds stale bytes that are never multiplied)
+        if (full) slice(2, 0, true, 3);
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         stg ^= 1;
         advance();
         __builtin_amdgcn_sched_barrier(0);
-        int na[4][2], nb[2][2];
-        read_scales(na, nb, stg);
-        read_frags(0, 0, smem + stg * STAGE);
+        slice(3, 2, full, 4);                             // (half step: the producer's transfers and the requests only)
         __builtin_amdgcn_sched_barrier(0);
-        slice(3, 2, full, sa, sb);                        // (half step: the producer's transfers only)
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int mt = 0; mt < 4; ++mt) { sa[mt][0] = na[mt][0]; sa[mt][1] = na[mt][1]; }
-#pragma unroll
-        for (int t = 0; t < 2; ++t) { sb[t][0] = nb[t][0]; sb[t][1] = nb[t][1]; }
+        take_scales();
 
         ++ks;
         if (last) {
