@@ -12,7 +12,7 @@ rank's experts), forced to the FP4 path.  Prints ONE JSON line.
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2|c3|c1]
                   [--no-cpu-baseline] [--detail PATH]
 
-Two further reports (each prints its own JSON line; weights are drawn on the device,
+Further reports (each prints its own JSON line; weights are drawn on the device,
 N(0, 0.02), because only timing is taken):
   --workload c4   8 simulated EP ranks run one after the other on the one GPU, 20 seeded
                   iterations with the vision skew redrawn, AIMD state carried: max-over-ranks
@@ -20,6 +20,15 @@ N(0, 0.02), because only timing is taken):
   --workload c5   48 layers with distinct BF16 weight sets on a Qwen3-VL-shaped rank, 65536
                   tokens: per-layer time with the weight encoding on the side stream, on the
                   main stream, and skipped (weights encoded beforehand) -> exposed encoding time.
+  --workload gate-sweep [--shape c2|c3]
+                  the measured rank's layer time with FP4 forced (weight encoding included) and with BF16
+                  forced, for batch sizes T = 64 .. 65536 (prefixes of one seeded batch): the smallest T from
+                  which FP4 stays faster is this machine's value of the LB gate Gamma.
+  --workload policy-ablation [--iterations N]
+                  the 8-rank simulation over a longer trace; every rank is timed in both precisions each
+                  iteration, and the policy variants (AIMD, fixed thresholds M = 0 and M = 0.7, decide-then-update,
+                  FP4 everywhere) are evaluated on the same measurements: max-rank layer ms and the share of
+                  rank-layers run in FP4.
 """
 from __future__ import annotations
 
@@ -42,8 +51,12 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"],
-                    help="c2 (default) is the headline line; c4 = 8-rank imbalance simulation, c5 = 48-layer overlap stress")
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "gate-sweep", "policy-ablation"],
+                    help="c2 (default) is the headline line; c4 = 8-rank imbalance simulation, c5 = 48-layer overlap stress, "
+                         "gate-sweep = FP4 vs BF16 layer time over the batch size (locates the LB gate), "
+                         "policy-ablation = AIMD / fixed-threshold variants on a longer simulated trace")
+    ap.add_argument("--shape", default="c2", choices=["c2", "c3"], help="layer shape of the gate sweep")
+    ap.add_argument("--iterations", type=int, default=100, help="trace length of the policy ablation")
     ap.add_argument("--precision", default="fp4", choices=["fp4", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--encode-mode", default="speculative", choices=["speculative", "side", "main"],
@@ -252,6 +265,153 @@ def run_c5(args):
     print(json.dumps(result))
 
 
+def run_gate_sweep(args):
+    """Batch-threshold study (the paper's LB gate, Sec. "LB Gate"): below some batch size the GEMMs no
+    longer dominate and switching to FP4, which costs the weight transformation, does not pay."""
+    import numpy as np
+    import torch
+    import workloads as W
+    import paper_2604_19503_amd as R
+    from paper_2604_19503_amd.binding import default_config
+    base = W.CONFIGS[args.shape]
+    T_max = 65536
+    cfg = W.scaled(base, T=T_max)
+    rcfg = default_config(T_max, cfg.E, cfg.k, cfg.D, cfg.H, cfg.I)
+    ctx = R.Context(rcfg)
+    buf = R.LayerBuffers(rcfg, T_max)
+    xb, isv_np = W.gen_tokens(cfg, 0)
+    logits_np = W.gen_logits(cfg, 0, isv_np)
+    x_all = R.bf16_from_bits(xb)
+    isv_all = torch.from_numpy(isv_np).cuda()
+    lg_all = torch.from_numpy(logits_np).cuda()
+    w13, w2 = _device_weights(torch, cfg.n_local, cfg.H, cfg.I, 300)
+    steps = max(5, min(args.steps, 30))
+    rows_out, gamma = [], None
+    for T in (64, 128, 256, 512, 1024, 2048, 4096, 8192, 16384, 32768, 65536):
+        x, isv, lg = x_all[:T], isv_all[:T], lg_all[:T]
+        ms = {}
+        for name, force, mode in (("bf16", R.BF16, 3), ("fp4", R.FP4, 3), ("fp4_side", R.FP4, 1)):
+            io = ctx.make_io(lg, isv, x, w13, w2, buf, cfg.rank, force=force, overlap=mode)
+            io.T = T
+            for _ in range(3):
+                ctx.layer_forward(io)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                ctx.layer_forward(io)
+            torch.cuda.synchronize()
+            ms[name] = (time.perf_counter() - t0) * 1e3 / steps
+        rows = int(buf.expert_offsets[-1].item())
+        rows_out.append({"T": T, "rows_on_rank": rows, "ms_bf16": round(ms["bf16"], 5), "ms_fp4": round(ms["fp4"], 5),
+                         "ms_fp4_encode_after_decision": round(ms["fp4_side"], 5),
+                         "fp4_speedup": round(ms["bf16"] / ms["fp4"], 3),
+                         "fp4_speedup_encode_after_decision": round(ms["bf16"] / ms["fp4_side"], 3)})
+    gamma_side = None
+    for r in reversed(rows_out):                      # smallest T from which FP4 stays faster
+        if r["fp4_speedup"] > 1.0:
+            gamma = r["T"]
+        else:
+            break
+    for r in reversed(rows_out):
+        if r["fp4_speedup_encode_after_decision"] > 1.0:
+            gamma_side = r["T"]
+        else:
+            break
+    result = {"metric": "LB gate on MI355X: smallest batch size T from which the FP4 layer (weight encoding included) stays faster than BF16",
+              "value": gamma, "unit": "tokens", "n_gpus": 1, "steps": steps, "warmup": 3, "ms_per_step": None,
+              "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16 vs fp4", "data": "synthetic",
+              "config": {"workload": f"gate-sweep on the {args.shape} layer shape ({cfg.E} experts top-{cfg.k}, {cfg.n_local} local, "
+                                     f"H={cfg.H} I={cfg.I}), hot rank, prefixes of one seeded 65536-token batch"},
+              "extra": {"gate_with_encoding_after_the_decision": gamma_side, "sweep": rows_out, "paper_context": "paper: Gamma = 2048 tokens (256 per rank x 8 ranks) on RTX 5090"}}
+    if args.detail:
+        with open(args.detail, "w") as f:
+            json.dump({"result": result}, f, indent=1)
+    ctx.close()
+    print(json.dumps(result))
+
+
+def run_policy_ablation(args):
+    """AIMD against the fixed-threshold variants (the paper's ReaLB-m1 / -m2) and the other update
+    order, on one longer simulated trace: every rank is timed in both precisions, so that all variants
+    are evaluated on identical measurements."""
+    import numpy as np
+    import torch
+    import workloads as W
+    import paper_2604_19503_amd as R
+    from paper_2604_19503_amd.binding import default_config, select_precision_host
+    cfg = W.CONFIGS["c4"]
+    iters = args.iterations
+    rcfg = default_config(cfg.T, cfg.E, cfg.k, cfg.D, cfg.H, cfg.I)
+    ctx = R.Context(rcfg)
+    buf = R.LayerBuffers(rcfg, cfg.T)
+    xb, isv_np = W.gen_tokens(cfg, 0)
+    x = R.bf16_from_bits(xb)
+    isv = torch.from_numpy(isv_np).cuda()
+    weights = [_device_weights(torch, cfg.n_local, cfg.H, cfg.I, 100 + d) for d in range(cfg.D)]
+    reps = 3
+    t_b = np.zeros((iters, cfg.D)); t_f = np.zeros((iters, cfg.D))
+    loads = np.zeros((iters, cfg.D), dtype=np.int64); viss = np.zeros((iters, cfg.D), dtype=np.int64)
+    kinds = []
+    for it in range(iters):
+        logits_np, info = W.gen_logits_trace(cfg, it, isv_np)
+        kinds.append(info["kind"])
+        lg = torch.from_numpy(logits_np).cuda()
+        ctx.route_stats(lg, isv, buf)
+        torch.cuda.synchronize()
+        loads[it] = buf.rank_load.cpu().numpy(); viss[it] = buf.rank_vis.cpu().numpy()
+        for d in range(cfg.D):
+            w13, w2 = weights[d]
+            io = ctx.make_io(lg, isv, x, w13, w2, buf, d, overlap=True)
+            for p, arr in ((R.BF16, t_b), (R.FP4, t_f)):
+                ctx.rank_forward(io, p)
+                arr[it, d], _ = event_ms(lambda: ctx.rank_forward(io, p), reps, torch)
+
+    def variant(name, aimd, M0, update_first, force=R.FORCE_NONE):
+        c = default_config(cfg.T, cfg.E, cfg.k, cfg.D, cfg.H, cfg.I)
+        c.aimd_enabled, c.M_init, c.update_first = aimd, M0, update_first
+        M, tmax, traj = M0, [], []
+        nf4 = {"calm": 0, "clustered": 0, "scattered": 0}
+        for it in range(iters):
+            prec, ib, M = select_precision_host(c, loads[it], viss[it], cfg.T, M, force)
+            t = np.where(np.asarray(prec) == R.FP4, t_f[it], t_b[it])
+            tmax.append(float(t.max())); nf4[kinds[it]] += int(np.sum(np.asarray(prec) == R.FP4)); traj.append(round(M, 3))
+        per_kind = {k: round(nf4[k] / max(1, kinds.count(k) * cfg.D), 4) for k in nf4}
+        ms_kind = {k: round(float(np.mean([tmax[i] for i in range(iters) if kinds[i] == k] or [0.0])), 5) for k in nf4}
+        return {"variant": name, "max_rank_ms": float(np.mean(tmax)), "max_rank_ms_by_regime": ms_kind,
+                "fp4_share_of_rank_layers": sum(nf4.values()) / (iters * cfg.D), "fp4_share_by_regime": per_kind,
+                "M_trajectory_first_40": traj[:40]}
+
+    base = float(np.mean(t_b.max(axis=1)))
+    variants = [variant("ReaLB (AIMD, update then decide)", 1, 0.9, 1),
+                variant("AIMD, decide then update", 1, 0.9, 0),
+                variant("fixed M = 0 (ReaLB-m1)", 0, 0.0, 1),
+                variant("fixed M = 0.7 (ReaLB-m2)", 0, 0.7, 1),
+                variant("fixed M = 0.9", 0, 0.9, 1),
+                variant("FP4 on every rank", 0, 0.9, 1, force=R.FP4)]
+    for v in variants:
+        v["speedup_vs_all_bf16"] = base / v["max_rank_ms"]
+    best = float(np.mean(np.minimum(t_b, t_f).max(axis=1)))
+    result = {"metric": "max-rank MoE layer ms over a simulated trace, AIMD policy",
+              "value": variants[0]["max_rank_ms"], "unit": "ms", "n_gpus": 1, "steps": iters, "warmup": 1,
+              "ms_per_step": variants[0]["max_rank_ms"], "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
+              "dtype": "bf16 / fp4 per rank (policy)", "data": "synthetic",
+              "config": {"workload": f"policy-ablation: c4's 8-rank layer over a {iters}-iteration trace whose imbalance comes and goes "
+                                     "(blocks of 10 iterations: calm / clustered / scattered), every rank timed in both precisions"},
+              "extra": {"max_rank_ms_all_bf16": base, "max_rank_ms_per_rank_minimum": best,
+                        "max_rank_ms_all_bf16_by_regime": {k: round(float(np.mean([t_b[i].max() for i in range(iters) if kinds[i] == k] or [0.0])), 5)
+                                                           for k in ("calm", "clustered", "scattered")},
+                        "ib_global_by_regime": {k: round(float(np.mean([loads[i].max() * cfg.D / (cfg.T * cfg.k) for i in range(iters) if kinds[i] == k] or [0.0])), 3)
+                                                for k in ("calm", "clustered", "scattered")},
+                        "variants": variants,
+                        "ib_global_mean": float(np.mean(loads.max(axis=1) * cfg.D / (cfg.T * cfg.k))),
+                        "paper_context": "paper: ReaLB 1.32x / m1 1.33x / m2 1.22x end to end on Kimi-VL MMMU; accuracy drops more with m1"}}
+    if args.detail:
+        with open(args.detail, "w") as f:
+            json.dump({"result": result}, f, indent=1)
+    ctx.close()
+    print(json.dumps(result))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -275,6 +435,10 @@ def main():
         return run_c4(args)
     if args.workload == "c5":
         return run_c5(args)
+    if args.workload == "gate-sweep":
+        return run_gate_sweep(args)
+    if args.workload == "policy-ablation":
+        return run_policy_ablation(args)
     cfg = W.CONFIGS[args.workload]
     fp4 = args.precision == "fp4"
     force = R.FP4 if fp4 else R.BF16

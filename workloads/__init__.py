@@ -21,7 +21,7 @@ import numpy as np
 
 __all__ = [
     "LayerShape", "CONFIGS", "f32_to_bf16_bits", "gen_tokens", "gen_weights",
-    "gen_logits", "gen_logits_c4", "gen_layer",
+    "gen_logits", "gen_logits_c4", "gen_logits_trace", "gen_layer",
 ]
 
 
@@ -169,6 +169,32 @@ def gen_logits_c4(cfg: LayerShape, iteration: int, is_vision: np.ndarray):
         hot = -1
         z[rng.permutation(cfg.E)] = np.arange(1, cfg.E + 1)
         beta, kind = 1.0, "scattered"
+    logits[vis] += _zipf_bias(cfg.E, cfg.zipf_s, beta, z)[None, :]
+    return logits, {"kind": kind, "hot_rank": hot, "beta": beta}
+
+
+def gen_logits_trace(cfg: LayerShape, iteration: int, is_vision: np.ndarray, block: int = 10):
+    """Per-iteration logits of a longer trace whose imbalance comes and goes (seed 2000+it), for
+    studying the threshold controller: blocks of `block` iterations cycle through "calm" (Zipf ranks
+    scattered over all experts, beta 0.1: device peak close to the mean), "clustered" (one uniformly
+    drawn hot rank, beta 0.5) and "scattered" (beta 1.0).  Returns (logits, info dict)."""
+    rng = np.random.default_rng([2000 + iteration, 43])
+    logits = rng.standard_normal((cfg.T, cfg.E), dtype=np.float32)
+    vis = is_vision.astype(bool)
+    nl = cfg.n_local
+    z = np.empty(cfg.E, dtype=np.int64)
+    regime = (iteration // block) % 3
+    if regime == 1:
+        hot = int(rng.integers(cfg.D))
+        local = np.arange(hot * nl, (hot + 1) * nl)
+        other = np.setdiff1d(np.arange(cfg.E), local)
+        z[rng.permutation(local)] = np.arange(1, nl + 1)
+        z[rng.permutation(other)] = np.arange(nl + 1, cfg.E + 1)
+        beta, kind = 0.5, "clustered"
+    else:
+        hot = -1
+        z[rng.permutation(cfg.E)] = np.arange(1, cfg.E + 1)
+        beta, kind = (0.1, "calm") if regime == 0 else (1.0, "scattered")
     logits[vis] += _zipf_bias(cfg.E, cfg.zipf_s, beta, z)[None, :]
     return logits, {"kind": kind, "hot_rank": hot, "beta": beta}
 
