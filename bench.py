@@ -62,7 +62,7 @@ def parse():
     ap.add_argument("--encode-mode", default="speculative", choices=["speculative", "side", "main"],
                     help="where the FP4 weight encoding runs: side stream before routing (fills the wait for the host's "
                          "decision; default), side stream after the decision (under the permutation), or main stream")
-    ap.add_argument("--gemm-tile", type=int, default=0, choices=[0, 2, 8], help="grouped-GEMM block tile selector (0 = automatic)")
+    ap.add_argument("--gemm-tile", type=int, default=0, choices=[0, 2, 8, 16], help="grouped-GEMM block tile selector (0 = automatic)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy (untimed) so that a counter run can scale FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--detail", default=None, help="write the per-kernel breakdown (JSON) to this path")

@@ -168,10 +168,12 @@ int realb_grouped_moe_ffn_down(realb_ctx* ctx, int prec, const int32_t* expert_o
                                long long max_rows, const void* h_mid, const uint8_t* h_s,
                                const void* w2, const uint8_t* w2_s, void* y_rows, void* stream);
 
-/* Tuning hook for the grouped GEMMs' block tile: 0 = automatic (default), 2 = 256x128
- * tiles with two blocks per CU, 8 = 256x256 tiles with 8 waves and one block per CU (used
- * only where the output width is a multiple of the tile).  Process-wide; outputs are
- * bit-identical for every choice (the accumulation order along K does not change). */
+/* Tuning hook for the grouped GEMMs' kernel: 0 = automatic (default: 16 where the output
+ * width is a multiple of its tile -- I % 128 == 0 for gate/up, H % 256 == 0 for down -- else 2),
+ * 16 = persistent 256x256 tiles fed by direct-to-LDS loads, 2 = register-staged 256x128
+ * tiles with two blocks per CU, 8 = register-staged 256x256 tiles with one block per CU.
+ * Process-wide; outputs are bit-identical for every choice (the accumulation order along K
+ * does not change).  REALB_EINVAL for any other value. */
 int realb_set_gemm_tile(int wn);
 
 /* Unpermute + weighted combine (local part of the result combination):
