@@ -24,6 +24,11 @@ N(0, 0.02), because only timing is taken):
                   the measured rank's layer time with FP4 forced (weight encoding included) and with BF16
                   forced, for batch sizes T = 64 .. 65536 (prefixes of one seeded batch): the smallest T from
                   which FP4 stays faster is this machine's value of the LB gate Gamma.
+  --workload format-gap
+                  quantization error (relative Frobenius, on the tensors and on a product X W^T) of MXFP4, the
+                  format the GEMMs run on, against the paper's NVFP4 (groups of 16, E4M3 scale, global scale),
+                  both encoded by this library's kernels, on synthetic weights, activations and a heavy-tailed
+                  tensor; and the two encoders' throughput.
   --workload policy-ablation [--iterations N]
                   the 8-rank simulation over a longer trace; every rank is timed in both precisions each
                   iteration, and the policy variants (AIMD, fixed thresholds M = 0 and M = 0.7, decide-then-update,
@@ -51,10 +56,11 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "gate-sweep", "policy-ablation"],
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "gate-sweep", "policy-ablation", "format-gap"],
                     help="c2 (default) is the headline line; c4 = 8-rank imbalance simulation, c5 = 48-layer overlap stress, "
                          "gate-sweep = FP4 vs BF16 layer time over the batch size (locates the LB gate), "
-                         "policy-ablation = AIMD / fixed-threshold variants on a longer simulated trace")
+                         "policy-ablation = AIMD / fixed-threshold variants on a longer simulated trace, "
+                         "format-gap = quantization error of the MXFP4 mapping against the paper's NVFP4")
     ap.add_argument("--shape", default="c2", choices=["c2", "c3"], help="layer shape of the gate sweep")
     ap.add_argument("--iterations", type=int, default=100, help="trace length of the policy ablation")
     ap.add_argument("--precision", default="fp4", choices=["fp4", "bf16"])
@@ -412,6 +418,77 @@ def run_policy_ablation(args):
     print(json.dumps(result))
 
 
+def run_format_gap(args):
+    """What the mapping of the paper's NVFP4 onto MXFP4 costs in accuracy, on synthetic tensors.  Both
+    encodings come from the library's kernels; decoding and the reference products are analysis code
+    (torch, FP32/FP64), not part of the product path."""
+    import numpy as np
+    import torch
+    import workloads as W
+    import paper_2604_19503_amd as R
+    from paper_2604_19503_amd.binding import scales_to_canonical
+    cfg = W.CONFIGS["c2"]
+    e2m1 = torch.tensor([0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0, -0.0, -0.5, -1.0, -1.5, -2.0, -3.0, -4.0, -6.0],
+                        dtype=torch.float64, device="cuda")
+
+    def codes_to_values(q):
+        lo, hi = (q & 0xF).long(), (q >> 4).long()
+        return torch.stack([e2m1[lo], e2m1[hi]], dim=-1).reshape(q.shape[0], -1)
+
+    def dec_mx(q, s, rows, K):
+        sc = torch.from_numpy(scales_to_canonical(s, rows, K).astype(np.int64)).cuda()
+        return (codes_to_values(q).reshape(rows, K // 32, 32) * torch.ldexp(torch.ones((), dtype=torch.float64, device="cuda"), sc - 127)[..., None]).reshape(rows, K)
+
+    def dec_nv(q, s, g, rows, K):
+        b = s.long()
+        e, m = b >> 3, b & 7
+        val = torch.where(e == 0, m.double() * 2.0 ** -9, (1 + m.double() / 8) * torch.ldexp(torch.ones((), dtype=torch.float64, device="cuda"), e - 7))
+        s_eff = (val.float() * np.float32(g)).double()
+        return (codes_to_values(q).reshape(rows, K // 16, 16) * s_eff[..., None]).reshape(rows, K)
+
+    rng = np.random.default_rng(77)
+    w = R.bf16_from_bits(W.gen_weights(cfg, 0, n_experts=1)[0][0])                        # [2I, H] ~ N(0, 0.02)
+    xa = R.bf16_from_bits(W.gen_tokens(W.scaled(cfg, T=4096), 0)[0])                       # [4096, H] ~ N(0, 1)
+    ht = rng.standard_normal((4096, cfg.H)).astype(np.float32)
+    ht[rng.integers(4096, size=400), rng.integers(cfg.H, size=400)] *= 30.0                # heavy tail: 0.005 % outliers x30
+    ht = R.bf16_from_bits(W.f32_to_bf16_bits(ht))
+    report = {}
+    dec = {}
+    for name, t in (("weights N(0,0.02)", w), ("activations N(0,1)", xa), ("activations with x30 outliers", ht)):
+        rows, K = t.shape
+        ref = t.double()
+        q, s = R.quantize_rows_fp4(t)
+        mx = dec_mx(q, s, rows, K)
+        g = float(np.float32(np.float32(float(R.amax_bf16(t).cpu()[0])) / np.float32(6.0 * 448.0)))
+        qn, sn = R.quantize_rows_nvfp4(t, g)
+        nv = dec_nv(qn, sn, g, rows, K)
+        dec[name] = (ref, mx, nv)
+        fro = lambda a: float(torch.linalg.norm(a - ref) / torch.linalg.norm(ref))
+        t_mx, _ = event_ms(lambda: R.quantize_rows_fp4(t), 20, torch)
+        t_nv, _ = event_ms(lambda: R.quantize_rows_nvfp4(t, g), 20, torch)
+        report[name] = {"shape": [rows, K], "rel_fro_error_mxfp4": fro(mx), "rel_fro_error_nvfp4": fro(nv),
+                        "bytes_per_element_mxfp4": 0.5 + 1 / 32, "bytes_per_element_nvfp4": 0.5 + 1 / 16,
+                        "encoder_gbs_mxfp4": rows * K * (2 + 0.5 + 1 / 32) / (t_mx * 1e-3) / 1e9,
+                        "encoder_gbs_nvfp4": rows * K * (2 + 0.5 + 1 / 16) / (t_nv * 1e-3) / 1e9}
+    prod = {}
+    for xname in ("activations N(0,1)", "activations with x30 outliers"):
+        xr, xm, xn = dec[xname]
+        wr, wm, wn = dec["weights N(0,0.02)"]
+        exact = xr @ wr.T
+        fro = lambda a: float(torch.linalg.norm(a - exact) / torch.linalg.norm(exact))
+        prod[xname + " x weights^T"] = {"rel_fro_error_mxfp4": fro(xm @ wm.T), "rel_fro_error_nvfp4": fro(xn @ wn.T)}
+    worst = max(v["rel_fro_error_mxfp4"] / v["rel_fro_error_nvfp4"] for v in prod.values())
+    result = {"metric": "W4A4 product error of MXFP4 relative to NVFP4 (ratio of relative Frobenius errors, worst case)",
+              "value": worst, "unit": "x", "n_gpus": 1, "steps": 20, "warmup": 1, "ms_per_step": None, "higher_is_better": False,
+              "scaling": "weak", "vs_baseline": None, "dtype": "fp4 encodings of bf16 tensors", "data": "synthetic",
+              "config": {"workload": "format-gap: Kimi-shaped expert weights [2816,2048], 4096 activation rows, and the same with outliers"},
+              "extra": {"tensors": report, "products": prod}}
+    if args.detail:
+        with open(args.detail, "w") as f:
+            json.dump({"result": result}, f, indent=1)
+    print(json.dumps(result))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -439,6 +516,8 @@ def main():
         return run_gate_sweep(args)
     if args.workload == "policy-ablation":
         return run_policy_ablation(args)
+    if args.workload == "format-gap":
+        return run_format_gap(args)
     cfg = W.CONFIGS[args.workload]
     fp4 = args.precision == "fp4"
     force = R.FP4 if fp4 else R.BF16

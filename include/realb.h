@@ -127,6 +127,22 @@ int realb_quantize_experts_fp4(realb_ctx* ctx, const void* w13, const void* w2, 
  * s u8 [rows,K/32] (K-step tiled).  No context needed. */
 int realb_quantize_rows_fp4(const void* x, long long rows, int K, uint8_t* q, uint8_t* s, void* stream);
 
+/* NVFP4-faithful variant of the encoder, for measuring what the mapping onto MXFP4 costs (paper
+ * Appendix "Implementation Details", Quantization Details: E2M1 elements, groups of 16, an FP8
+ * E4M3 scale per group from the group's absolute maximum / 6.0 and a global scale, rounded into
+ * FP8 and clamped, values mapped to the nearest FP4 value).  No GEMM of this library reads it.
+ *   x bf16 [rows, K] (K multiple of 16), global_scale > 0 (host scalar; the usual choice is the
+ *   tensor's max |x| / (6 * 448), see realb_amax_bf16)
+ *   q u8 [rows, K/2] codes as above;  s u8 [rows, K/16] E4M3 bytes (bias 7, max 448), plain row-major.
+ * Rounding decisions in IEEE binary32: s_local = amax/6, r = s_local/global_scale, byte = nearest-even
+ * E4M3(r) clamped to 448, s_eff = E4M3(byte)*global_scale, code = nearest-even E2M1(|x|/s_eff), saturating;
+ * a group whose scale rounds to 0 gets byte 0 and zero magnitudes; sign bits are kept. */
+int realb_quantize_rows_nvfp4(const void* x, long long rows, int K, float global_scale, uint8_t* q, uint8_t* s,
+                              void* stream);
+
+/* max |x| over n BF16 elements (n multiple of 8) as a float, written to *amax (device). */
+int realb_amax_bf16(const void* x, long long n, float* amax, void* stream);
+
 /* Token permutation / dispatch packing for rank `rank` (the local stand-in for
  * the all-to-all dispatch of Sec. "Overhead-Aware Pipeline Orchestration").
  * Rows are this rank's assignments sorted by (local expert, a = t*k + j).

@@ -86,10 +86,11 @@ def quantize(bits: np.ndarray, g):
     vb = np.abs(v).astype(np.float32).reshape(bits.shape[:-1] + (K // GROUP, GROUP))    # BF16 values are exact in FP32
     amax = vb.max(axis=-1)
     s_local = (amax / np.float32(6.0)).astype(np.float32)
-    r = (s_local / g).astype(np.float32)
+    with np.errstate(over="ignore"):                       # an overflowing quotient is +inf: clamps to 448 / saturates to 6
+        r = (s_local / g).astype(np.float32)
     byte = e4m3_round(r)
     s_eff = (e4m3_values()[byte].astype(np.float32) * g).astype(np.float32)
-    with np.errstate(divide="ignore", invalid="ignore"):
+    with np.errstate(divide="ignore", invalid="ignore", over="ignore"):
         q = (vb / s_eff[..., None]).astype(np.float32)
     mag = np.where(s_eff[..., None] == 0, np.uint8(0), e2m1_round_mag_f32(np.where(s_eff[..., None] == 0, 0, q)))
     sign = ((bits >> np.uint16(15)) & np.uint16(1)).astype(np.uint8).reshape(vb.shape)

@@ -16,6 +16,7 @@ EXPORTS = [
     "realb_route_stats", "realb_select_precision", "realb_select_precision_host", "realb_quantize_experts_fp4",
     "realb_quantize_rows_fp4", "realb_permute", "realb_grouped_moe_ffn", "realb_grouped_moe_ffn_gate_up",
     "realb_grouped_moe_ffn_down", "realb_set_gemm_tile", "realb_combine", "realb_layer_forward", "realb_rank_forward",
+    "realb_quantize_rows_nvfp4", "realb_amax_bf16",
 ]
 
 
@@ -79,6 +80,8 @@ def load_library() -> C.CDLL:
     lib.realb_combine.argtypes = [vp, vp, vp, vp, C.c_int, vp, vp]
     lib.realb_layer_forward.argtypes = [vp, C.POINTER(LayerIO), vp]
     lib.realb_rank_forward.argtypes = [vp, C.POINTER(LayerIO), C.c_int, vp]
+    lib.realb_quantize_rows_nvfp4.argtypes = [vp, C.c_longlong, C.c_int, C.c_float, vp, vp, vp]
+    lib.realb_amax_bf16.argtypes = [vp, C.c_longlong, vp, vp]
     _LIB = lib
     return lib
 
@@ -151,6 +154,22 @@ def quantize_rows_fp4(x: torch.Tensor, stream=None):
     q = torch.empty((rows, K // 2), dtype=torch.uint8, device=x.device)
     s = torch.zeros((-(-rows // 32) * 32, K // 32), dtype=torch.uint8, device=x.device)
     _check(load_library().realb_quantize_rows_fp4(_p(x), rows, K, _p(q), _p(s), _stream(stream)))
+    return q, s
+
+
+def amax_bf16(x: torch.Tensor, stream=None) -> torch.Tensor:
+    """realb_amax_bf16: max |x| of a bf16 tensor (element count a multiple of 8) as a 1-element float tensor."""
+    out = torch.empty(1, dtype=torch.float32, device=x.device)
+    _check(load_library().realb_amax_bf16(_p(x), x.numel(), _p(out), _stream(stream)))
+    return out
+
+
+def quantize_rows_nvfp4(x: torch.Tensor, global_scale: float, stream=None):
+    """realb_quantize_rows_nvfp4 on a bf16 [rows,K] tensor -> (q u8 [rows,K/2], s u8 [rows,K/16] E4M3 bytes)."""
+    rows, K = x.shape
+    q = torch.empty((rows, K // 2), dtype=torch.uint8, device=x.device)
+    s = torch.empty((rows, K // 16), dtype=torch.uint8, device=x.device)
+    _check(load_library().realb_quantize_rows_nvfp4(_p(x), rows, K, C.c_float(global_scale), _p(q), _p(s), _stream(stream)))
     return q, s
 
 

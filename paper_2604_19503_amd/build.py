@@ -9,7 +9,7 @@ import sys
 PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "librealb.so")
-SOURCES = ["context.hip", "quantize.hip", "route_stats.hip", "permute.hip", "ffn.hip", "combine.hip", "layer.hip"]
+SOURCES = ["context.hip", "quantize.hip", "route_stats.hip", "permute.hip", "ffn.hip", "combine.hip", "layer.hip", "nvfp4.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
