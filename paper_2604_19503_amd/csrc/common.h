@@ -25,11 +25,17 @@ struct Ctx {
     int32_t* stats_host;   // [2*D]
     hipStream_t side;      // side stream for the weight encoder
     hipEvent_t ev_fork, ev_join;
+    hipEvent_t ev_stats;   // recorded behind the histogram reduce: the host's cue that the routing statistics are in stats_host
 };
 
 void set_error(const char* fmt, ...);
+// Waits for `ready` (an event recorded behind the kernel that fills stats_host), then evaluates the policy.
 int select_precision_pinned(Ctx* c, int T, int force, int32_t* prec_host, double* ib_global_host, double* M_after_host,
-                            hipStream_t s);
+                            hipEvent_t ready);
+int permute_indices(Ctx* c, const int32_t* topk_ids, int T, int rank, long long max_rows, int32_t* expert_offsets,
+                    int32_t* row_to_assign, int32_t* assign_to_row, hipStream_t s);
+int permute_gather(Ctx* c, const void* x, const int32_t* assign_to_row, int T, int prec, void* x_perm, uint8_t* x_q,
+                   uint8_t* x_s, hipStream_t s);
 int hip_fail(hipError_t e, const char* what);
 
 #define REALB_HIP(call)                                                        \

@@ -70,8 +70,8 @@ static void policy(const realb_config& c, const int32_t* load, const int32_t* vi
 
 // Policy on the pinned host copy of the statistics that the last realb_route_stats on `stream` wrote.
 int select_precision_pinned(Ctx* c, int T, int force, int32_t* prec_host, double* ib_global_host, double* M_after_host,
-                            hipStream_t s) {
-    REALB_HIP(hipStreamSynchronize(s));
+                            hipEvent_t ready) {
+    REALB_HIP(hipEventSynchronize(ready));
     policy(c->cfg, c->stats_host, c->stats_host + c->cfg.D, T, force, &c->M, prec_host, ib_global_host);
     if (M_after_host) *M_after_host = c->M;
     return REALB_OK;
@@ -103,17 +103,18 @@ int realb_create(const realb_config* cfg, realb_ctx** out) {
     c->cfg = *cfg;
     c->n_local = cfg->E / cfg->D;
     c->M = cfg->M_init;
-    c->wave_cnt = nullptr; c->hist_part = nullptr; c->stats_host = nullptr; c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr;
+    c->wave_cnt = nullptr; c->hist_part = nullptr; c->stats_host = nullptr; c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr; c->ev_stats = nullptr;
     hipError_t e = hipGetDevice(&c->device);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&c->num_cus, hipDeviceAttributeMultiprocessorCount, c->device);
     long long A_max = (long long)cfg->T_max * cfg->k;
     c->n_chunks_max = ceil_div(A_max, kPermChunk) + 1;
     if (e == hipSuccess) e = hipMalloc((void**)&c->wave_cnt, (size_t)c->n_chunks_max * c->n_local * sizeof(int32_t));
-    if (e == hipSuccess) e = hipMalloc((void**)&c->hist_part, (size_t)c->num_cus * 2 * cfg->E * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void**)&c->hist_part, (size_t)c->num_cus * 2 * 2 * cfg->E * sizeof(int32_t));   // two blocks per CU x [2][E]
     if (e == hipSuccess) e = hipHostMalloc((void**)&c->stats_host, 2 * cfg->D * sizeof(int32_t), hipHostMallocDefault);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_stats, hipEventDisableTiming);
     if (e != hipSuccess) {
         realb_destroy(reinterpret_cast<realb_ctx*>(c));
         return hip_fail(e, "realb_create");
@@ -130,6 +131,7 @@ int realb_destroy(realb_ctx* ctx) {
     if (c->stats_host) (void)hipHostFree(c->stats_host);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
+    if (c->ev_stats) (void)hipEventDestroy(c->ev_stats);
     if (c->side) (void)hipStreamDestroy(c->side);
     delete c;
     return REALB_OK;

@@ -8,8 +8,9 @@
 using namespace realb;
 
 // quant_in_flight: the weight encoding was already issued on the side stream (speculative mode)
-// and ev_join marks its end.
-static int rank_forward_impl(realb_ctx* ctx, realb_layer_io* io, int prec, void* stream, bool quant_in_flight) {
+// and ev_join marks its end.  indices_done: the permutation's index kernels are already on the stream.
+static int rank_forward_impl(realb_ctx* ctx, realb_layer_io* io, int prec, void* stream, bool quant_in_flight,
+                             bool indices_done) {
     REALB_REQUIRE(ctx && io, REALB_EINVAL, "NULL argument");
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     REALB_REQUIRE(prec == REALB_BF16 || prec == REALB_FP4, REALB_EINVAL, "bad precision %d", prec);
@@ -30,8 +31,12 @@ static int rank_forward_impl(realb_ctx* ctx, realb_layer_io* io, int prec, void*
             if (rc != REALB_OK) return rc;
         }
     }
-    rc = realb_permute(ctx, io->x, io->topk_ids, io->T, io->rank, prec, io->max_rows, io->expert_offsets, io->row_to_assign,
-                       io->assign_to_row, io->x_perm, io->x_q, io->x_s, stream);
+    if (!indices_done) {
+        rc = permute_indices(c, io->topk_ids, io->T, io->rank, io->max_rows, io->expert_offsets, io->row_to_assign,
+                             io->assign_to_row, s);
+        if (rc != REALB_OK) return rc;
+    }
+    rc = permute_gather(c, io->x, io->assign_to_row, io->T, prec, io->x_perm, io->x_q, io->x_s, s);
     if (rc != REALB_OK) return rc;
     if (fp4 && side) REALB_HIP(hipStreamWaitEvent(s, c->ev_join, 0));
     if (fp4)
@@ -49,7 +54,7 @@ static int rank_forward_impl(realb_ctx* ctx, realb_layer_io* io, int prec, void*
 }
 
 extern "C" int realb_rank_forward(realb_ctx* ctx, realb_layer_io* io, int prec, void* stream) {
-    return rank_forward_impl(ctx, io, prec, stream, false);
+    return rank_forward_impl(ctx, io, prec, stream, false, false);
 }
 
 extern "C" int realb_layer_forward(realb_ctx* ctx, realb_layer_io* io, void* stream) {
@@ -75,7 +80,14 @@ extern "C" int realb_layer_forward(realb_ctx* ctx, realb_layer_io* io, void* str
     if (rc != REALB_OK) return rc;
     REALB_REQUIRE(io->force == REALB_FORCE_NONE || io->force == REALB_BF16 || io->force == REALB_FP4, REALB_EINVAL,
                   "bad force value %d", io->force);
-    rc = select_precision_pinned(c, io->T, io->force, io->prec_host, &io->ib_global, &io->M_after, as_stream(stream));
+    // The statistics reach pinned host memory with the histogram reduce.  The permutation's index
+    // kernels do not depend on the precision, so they go out first and run while the host waits for
+    // the event, takes the decision and launches the rest: the GPU does not idle across the decision.
+    REALB_HIP(hipEventRecord(c->ev_stats, as_stream(stream)));
+    rc = permute_indices(c, io->topk_ids, io->T, io->rank, io->max_rows, io->expert_offsets, io->row_to_assign,
+                         io->assign_to_row, as_stream(stream));
     if (rc != REALB_OK) return rc;
-    return rank_forward_impl(ctx, io, io->prec_host[io->rank], stream, speculative);
+    rc = select_precision_pinned(c, io->T, io->force, io->prec_host, &io->ib_global, &io->M_after, c->ev_stats);
+    if (rc != REALB_OK) return rc;
+    return rank_forward_impl(ctx, io, io->prec_host[io->rank], stream, speculative, true);
 }

@@ -170,34 +170,59 @@ static void launch_gather(int blocks, hipStream_t s, const void* x, const int32_
 
 using namespace realb;
 
-extern "C" int realb_permute(realb_ctx* ctx, const void* x, const int32_t* topk_ids, int T, int rank, int prec,
-                             long long max_rows, int32_t* expert_offsets, int32_t* row_to_assign, int32_t* assign_to_row,
-                             void* x_perm, uint8_t* x_q, uint8_t* x_s, void* stream) {
-    REALB_REQUIRE(ctx && expert_offsets, REALB_EINVAL, "NULL argument");
-    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+namespace realb {
+
+// The two halves of realb_permute.  The index half (count / scan / rank) does not depend on the
+// precision, so the layer can run it while the host is still taking the precision decision.
+int permute_indices(Ctx* c, const int32_t* topk_ids, int T, int rank, long long max_rows, int32_t* expert_offsets,
+                    int32_t* row_to_assign, int32_t* assign_to_row, hipStream_t s) {
+    REALB_REQUIRE(c && expert_offsets, REALB_EINVAL, "NULL argument");
     REALB_REQUIRE(T >= 0 && T <= c->cfg.T_max, REALB_ECAP, "T=%d outside [0, T_max=%d]", T, c->cfg.T_max);
     REALB_REQUIRE(rank >= 0 && rank < c->cfg.D, REALB_EINVAL, "rank=%d outside [0,%d)", rank, c->cfg.D);
-    REALB_REQUIRE(prec == REALB_BF16 || prec == REALB_FP4, REALB_EINVAL, "bad precision %d", prec);
-    const int k = c->cfg.k, n_local = c->n_local, H = c->cfg.H;
+    const int k = c->cfg.k, n_local = c->n_local;
     const long long A = (long long)T * k;
     const long long worst = (long long)T * (k < n_local ? k : n_local);
     REALB_REQUIRE(max_rows >= worst, REALB_EINVAL, "max_rows=%lld is below the worst case %lld", max_rows, worst);
-    REALB_REQUIRE(T == 0 || (x && topk_ids && row_to_assign && assign_to_row), REALB_EINVAL, "NULL argument");
-    REALB_REQUIRE(T == 0 || (prec == REALB_BF16 ? x_perm != nullptr : (x_q && x_s)), REALB_EINVAL, "NULL row buffer");
-    hipStream_t s = as_stream(stream);
+    REALB_REQUIRE(T == 0 || (topk_ids && row_to_assign && assign_to_row), REALB_EINVAL, "NULL argument");
     const int n_chunks = ceil_div(A, kPermChunk);
     const int lo = rank * n_local;
     const int chunk_blocks = ceil_div(n_chunks, 4);
     if (n_chunks > 0)
         hipLaunchKernelGGL(perm_count_kernel, dim3(chunk_blocks), dim3(256), 0, s, topk_ids, (int)A, lo, n_local, n_chunks, c->wave_cnt);
     hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, s, c->wave_cnt, n_chunks, n_local, expert_offsets);
-    if (n_chunks > 0) {
+    if (n_chunks > 0)
         hipLaunchKernelGGL(perm_rank_kernel, dim3(chunk_blocks), dim3(256), 0, s, topk_ids, (int)A, lo, n_local, n_chunks,
                            c->wave_cnt, expert_offsets, row_to_assign, assign_to_row);
-        const int blocks = T < 4 ? 1 : (T / 4 < 256 * 16 ? T / 4 : 256 * 16);
-        if (prec == REALB_FP4) launch_gather<true>(blocks, s, x, assign_to_row, T, k, H, nullptr, x_q, x_s);
-        else launch_gather<false>(blocks, s, x, assign_to_row, T, k, H, x_perm, nullptr, nullptr);
-    }
     REALB_HIP(hipGetLastError());
     return REALB_OK;
+}
+
+int permute_gather(Ctx* c, const void* x, const int32_t* assign_to_row, int T, int prec, void* x_perm, uint8_t* x_q,
+                   uint8_t* x_s, hipStream_t s) {
+    REALB_REQUIRE(c != nullptr, REALB_EINVAL, "NULL argument");
+    REALB_REQUIRE(prec == REALB_BF16 || prec == REALB_FP4, REALB_EINVAL, "bad precision %d", prec);
+    REALB_REQUIRE(T >= 0 && T <= c->cfg.T_max, REALB_ECAP, "T=%d outside [0, T_max=%d]", T, c->cfg.T_max);
+    if (T == 0) return REALB_OK;
+    REALB_REQUIRE(x && assign_to_row, REALB_EINVAL, "NULL argument");
+    REALB_REQUIRE(prec == REALB_BF16 ? x_perm != nullptr : (x_q && x_s), REALB_EINVAL, "NULL row buffer");
+    const int k = c->cfg.k, H = c->cfg.H;
+    const int blocks = T < 4 ? 1 : (T / 4 < 256 * 16 ? T / 4 : 256 * 16);
+    if (prec == REALB_FP4) launch_gather<true>(blocks, s, x, assign_to_row, T, k, H, nullptr, x_q, x_s);
+    else launch_gather<false>(blocks, s, x, assign_to_row, T, k, H, x_perm, nullptr, nullptr);
+    REALB_HIP(hipGetLastError());
+    return REALB_OK;
+}
+
+}  // namespace realb
+
+extern "C" int realb_permute(realb_ctx* ctx, const void* x, const int32_t* topk_ids, int T, int rank, int prec,
+                             long long max_rows, int32_t* expert_offsets, int32_t* row_to_assign, int32_t* assign_to_row,
+                             void* x_perm, uint8_t* x_q, uint8_t* x_s, void* stream) {
+    REALB_REQUIRE(ctx != nullptr, REALB_EINVAL, "NULL argument");
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    REALB_REQUIRE(prec == REALB_BF16 || prec == REALB_FP4, REALB_EINVAL, "bad precision %d", prec);
+    REALB_REQUIRE(T <= 0 || (x && (prec == REALB_BF16 ? x_perm != nullptr : (x_q && x_s))), REALB_EINVAL, "NULL row buffer");
+    int rc = permute_indices(c, topk_ids, T, rank, max_rows, expert_offsets, row_to_assign, assign_to_row, as_stream(stream));
+    if (rc != REALB_OK) return rc;
+    return permute_gather(c, x, assign_to_row, T, prec, x_perm, x_q, x_s, as_stream(stream));
 }

@@ -42,7 +42,7 @@ __device__ __forceinline__ float wave_max(float v) {
 // The block's histograms live in LDS; each block writes its partial histogram to the workspace
 // (no global atomics, no pre-zeroing), and a one-block kernel adds the partials up.
 template <int EPL>
-__global__ void __launch_bounds__(1024) topk_hist_kernel(const float* __restrict__ logits, const uint8_t* __restrict__ is_vision,
+__global__ void __launch_bounds__(1024, 2) topk_hist_kernel(const float* __restrict__ logits, const uint8_t* __restrict__ is_vision,
                                                         int T, int E, int k, int32_t* __restrict__ topk_ids,
                                                         float* __restrict__ topk_w, int32_t* __restrict__ hist_part) {
     extern __shared__ int32_t hist[];                 // [2*E]: counts, vision counts
@@ -52,12 +52,27 @@ __global__ void __launch_bounds__(1024) topk_hist_kernel(const float* __restrict
     const int wave = threadIdx.x >> 6;
     const int waves_per_block = blockDim.x >> 6;
     const float NEG = -INFINITY;
-    for (int t = blockIdx.x * waves_per_block + wave; t < T; t += gridDim.x * waves_per_block) {
-        float v[EPL];
-        const float* row = logits + (size_t)t * E + lane * EPL;
+    // The wave's next token is fetched while the current one is being ranked (one load latency per
+    // wave instead of one per token).
+    const int stride = gridDim.x * waves_per_block;
+    int t = blockIdx.x * waves_per_block + wave;
+    float nx[EPL];
+    int nx_vision = 0;
+    auto fetch = [&](int tok) __attribute__((always_inline)) {
+        if (tok < T) {
+            const float* row = logits + (size_t)tok * E + lane * EPL;
 #pragma unroll
-        for (int j = 0; j < EPL; ++j) v[j] = (lane * EPL + j < E) ? row[j] : NEG;
-        const int vision = is_vision[t];
+            for (int j = 0; j < EPL; ++j) nx[j] = (lane * EPL + j < E) ? row[j] : NEG;
+            nx_vision = is_vision[tok];
+        }
+    };
+    fetch(t);
+    for (; t < T; t += stride) {
+        float v[EPL];
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) v[j] = nx[j];
+        const int vision = nx_vision;
+        fetch(t + stride);
         float my_val = 0.f;                           // lane j keeps the j-th selected logit
         int my_id = 0;                                //        and its expert index
         for (int sel = 0; sel < k; ++sel) {
@@ -142,7 +157,7 @@ extern "C" int realb_route_stats(realb_ctx* ctx, const float* logits, const uint
     const int E = c->cfg.E, k = c->cfg.k, D = c->cfg.D;
     int blocks = 0;
     if (T > 0) {
-        blocks = min(ceil_div(T, 16), c->num_cus);          // 16 waves (tokens in flight) per block
+        blocks = min(ceil_div(T, 16), 2 * c->num_cus);      // 16 waves (tokens in flight) per block, two blocks per CU
         const size_t lds = 2 * (size_t)E * sizeof(int32_t);
         const int epl = ceil_div(E, 64);
 #define REALB_TOPK(EPL)                                                                                      \
