@@ -396,6 +396,39 @@ def test_edge_empty_batch_and_empty_rank_and_empty_expert(R):
     ctx.close()
 
 
+def test_edge_sixty_four_local_experts_some_empty(R):
+    """One rank holding 64 experts (the supported maximum), several of them without tokens and several
+    with a handful: the GEMMs' expert table, tiles that hold one or two rows, and empty segments."""
+    from paper_2604_19503_amd.binding import default_config
+    cfg = W.scaled(W.CONFIGS["c1"], E=64, D=1, k=4, T=700, H=256, I=128)
+    rcfg = default_config(cfg.T, cfg.E, cfg.k, cfg.D, cfg.H, cfg.I)
+    ctx = R.Context(rcfg)
+    rng = np.random.default_rng(31)
+    inp = W.gen_layer(cfg, 7)
+    logits = rng.standard_normal((cfg.T, cfg.E)).astype(np.float32)
+    logits[:, 5] = -100.0; logits[:, 17:20] = -100.0; logits[:, 63] = -100.0      # empty experts, also the last one
+    logits[:, 40] -= 1.0                                                          # an expert with one or two tokens
+    logits[:, 2] += 2.5                                                           # a hot one: several row tiles
+    inp["logits"] = logits
+    w13b, w2b = W.gen_weights(cfg, 7, n_experts=cfg.E)
+    x = R.bf16_from_bits(inp["x"]); w13 = R.bf16_from_bits(w13b); w2 = R.bf16_from_bits(w2b)
+    lg = torch.from_numpy(logits).cuda(); isv = torch.from_numpy(inp["is_vision"]).cuda()
+    for prec in (R.BF16, R.FP4):
+        _say(f"64 local experts prec={prec}")
+        b = R.LayerBuffers(rcfg, cfg.T)
+        io = ctx.make_io(lg, isv, x, w13, w2, b, 0, force=prec)
+        assert ctx.layer_forward(io) == prec
+        _sync()
+        o = olayer.rank_layer(dict(inp, w13=w13b, w2=w2b), cfg.E, cfg.k, cfg.D, 0, 0.9, force=prec)
+        assert same(b.expert_offsets.cpu().numpy(), o["expert_offsets"])
+        assert same(b.assign_to_row.cpu().numpy(), o["assign_to_row"])
+        cnt = np.diff(o["expert_offsets"])
+        assert (cnt == 0).sum() >= 5 and cnt.max() > 256 and 0 < cnt[40] < 8
+        out = obf.bits_to_f64(R.bits_from_bf16(b.out))
+        assert rel_fro(out, o["out"]) <= (2 * FP4_TOL if prec == R.FP4 else BF16_TOL)
+    ctx.close()
+
+
 def test_capacity_and_argument_errors(R, case):
     b = case.buf
     big = torch.empty((case.cfg.T + 1, case.cfg.E), dtype=torch.float32, device="cuda")
