@@ -133,6 +133,9 @@ __device__ __forceinline__ TileInfo decode_tile(const GemmParams& p, int tile, i
 // lanes therefore swap halves (DPP quad permute), so that one instruction writes the even rows and the
 // next the odd rows, four lanes covering 64 contiguous bytes of a row: 16 rows per instruction, ~3x the
 // store rate measured.  `base` points at column 0 of tile row 0; rows >= rows_left are not written.
+// NT: non-temporal stores -- measured faster on the BF16 path (whose operand stream already overflows
+// the L2) and slower on the FP4 path.
+template <bool NT>
 __device__ __forceinline__ void store_tile_rows(uint8_t* base, size_t row_pitch, int lane, int rows_left,
                                                 const u32x4_t& c0, const u32x4_t& c1) {
     const int li = lane & 31, half = lane >> 5;
@@ -151,8 +154,13 @@ __device__ __forceinline__ void store_tile_rows(uint8_t* base, size_t row_pitch,
     rb = u32x4_t{xb[0], xb[1], xb[2], xb[3]};
     const int row_a = li & ~1;
     uint8_t* dst = base + (size_t)row_a * row_pitch + (half * 2 + (lane & 1)) * 16;
-    if (row_a < rows_left) *reinterpret_cast<u32x4_t*>(dst) = ra;
-    if (row_a + 1 < rows_left) *reinterpret_cast<u32x4_t*>(dst + row_pitch) = rb;
+    if constexpr (NT) {
+        if (row_a < rows_left) __builtin_nontemporal_store(ra, reinterpret_cast<u32x4_t*>(dst));
+        if (row_a + 1 < rows_left) __builtin_nontemporal_store(rb, reinterpret_cast<u32x4_t*>(dst + row_pitch));
+    } else {
+        if (row_a < rows_left) *reinterpret_cast<u32x4_t*>(dst) = ra;
+        if (row_a + 1 < rows_left) *reinterpret_cast<u32x4_t*>(dst + row_pitch) = rb;
+    }
 }
 
 // Epilogue, straight from registers.  acc[mt][t][r] belongs to activation row wm*128 + mt*32 + li
@@ -193,7 +201,7 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, v16f_t (&acc)[4][W
                     }
                 } else {
                     const int tile_row0 = wm * 128 + mt * 32;
-                    store_tile_rows(p.out + ((size_t)(row0 + tile_row0) * p.n_out + ctile) * 2, (size_t)p.n_out * 2, lane,
+                    store_tile_rows<true>(p.out + ((size_t)(row0 + tile_row0) * p.n_out + ctile) * 2, (size_t)p.n_out * 2, lane,
                                     rows_valid - tile_row0, u32x4_t{hb[0], hb[1], hb[2], hb[3]}, u32x4_t{hb[4], hb[5], hb[6], hb[7]});
                 }
             }
@@ -205,7 +213,7 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, v16f_t (&acc)[4][W
 #pragma unroll
             for (int t = 0; t < WN; ++t) {
                 const int col0 = n0 + wn * WN * 32 + t * 32;
-                store_tile_rows(p.out + ((size_t)(row0 + tile_row0) * p.n_out + col0) * 2, (size_t)p.n_out * 2, lane,
+                store_tile_rows<!FP4>(p.out + ((size_t)(row0 + tile_row0) * p.n_out + col0) * 2, (size_t)p.n_out * 2, lane,
                                 rows_valid - tile_row0,
                                 u32x4_t{pack_bf16x2(acc[mt][t][0], acc[mt][t][1]), pack_bf16x2(acc[mt][t][2], acc[mt][t][3]),
                                         pack_bf16x2(acc[mt][t][4], acc[mt][t][5]), pack_bf16x2(acc[mt][t][6], acc[mt][t][7])},
