@@ -426,11 +426,12 @@ __global__ void __launch_bounds__(128 * WGN, MINB) ffn_gemm_kernel(const GemmPar
 //     row the eight 16-byte parts are XOR-swizzled by (row>>1)&7 (done on the global address of
 //     each lane, since the LDS side of the transfer is fixed), which makes the 32-row x 16-byte
 //     fragment reads bank-conflict free;
-//   - paces the loads between the MFMAs of the middle K-slices (a wave blocks while the memory
-//     pipeline accepts an instruction, and eight waves issuing at once stall all MFMA issue);
-//   - is persistent: a block walks its XCD's tile range, and the last K-step of a tile already
-//     fetches the first K-step of the next one, so only the register-only epilogue sits between
-//     two tiles' MFMA streams;
+//   - spreads the transfer instructions between MFMAs (a wave blocks while the memory pipeline accepts
+//     an instruction, and eight waves issuing at once stall all MFMA issue) and keeps the producer a
+//     whole K-step ahead, so that no transfer is waited for;
+//   - is persistent: a block walks its XCD's tile range and its producer runs across tile boundaries
+//     (the expert table sits in LDS, so switching tiles touches no global memory); only the
+//     register-only epilogue sits between two tiles' MFMA streams;
 //   - FP4: stages the E8M0 scales through LDS as well (global_load_lds_dword, 32 rows x 2 dwords
 //     per instruction), because one vector-memory instruction per lane-dword costs as much issue
 //     time as a 1-KB one.
@@ -454,8 +455,6 @@ __device__ __forceinline__ void lds_dma4(const uint32_t* g, uint8_t* l) {
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
                                      (__attribute__((address_space(3))) void*)l, 4, 0, 0);
 }
-
-template <int N> struct IntC { static constexpr int value = N; };
 
 template <bool FP4, bool GATEUP>
 __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p) {
