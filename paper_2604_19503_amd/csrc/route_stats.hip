@@ -107,6 +107,80 @@ __global__ void __launch_bounds__(1024, 2) topk_hist_kernel(const float* __restr
     for (int i = threadIdx.x; i < 2 * E; i += blockDim.x) hist_part[(size_t)blockIdx.x * 2 * E + i] = hist[i];
 }
 
+__device__ __forceinline__ int row_min_i(int v) {
+    v = min(v, __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false));
+    v = min(v, __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false));
+    v = min(v, __builtin_amdgcn_update_dpp(v, v, 0x141, 0xF, 0xF, false));
+    v = min(v, __builtin_amdgcn_update_dpp(v, v, 0x140, 0xF, 0xF, false));
+    return v;
+}
+
+// Four tokens per wave (E <= 128, a multiple of 16): a row of 16 lanes owns one token, lane j of the
+// row holds the EPL = E/16 consecutive experts j*EPL .. j*EPL+EPL-1.  A selection round is the lane's
+// best, the row maximum, and the row minimum of the expert index among the lanes that hold that
+// maximum (lowest index wins ties) -- DPP only, no scalar round trips, the four rows in lock step.
+template <int EPL>
+__global__ void __launch_bounds__(1024, 2) topk_hist_rows_kernel(const float* __restrict__ logits, const uint8_t* __restrict__ is_vision,
+                                                                 int T, int E, int k, int32_t* __restrict__ topk_ids,
+                                                                 float* __restrict__ topk_w, int32_t* __restrict__ hist_part) {
+    extern __shared__ int32_t hist[];                 // [2*E]: counts, vision counts
+    for (int i = threadIdx.x; i < 2 * E; i += blockDim.x) hist[i] = 0;
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int j = lane & 15, r = lane >> 4;
+    const int wave = threadIdx.x >> 6;
+    const int waves_per_block = blockDim.x >> 6;
+    const float NEG = -INFINITY;
+    const int stride = gridDim.x * waves_per_block * 4;
+    int t = (blockIdx.x * waves_per_block + wave) * 4 + r;
+    float nx[EPL];
+    int nx_vision = 0;
+    auto fetch = [&](int tok) __attribute__((always_inline)) {
+        if (tok < T) {
+            const float* row = logits + (size_t)tok * E + j * EPL;
+#pragma unroll
+            for (int q = 0; q < EPL; ++q) nx[q] = row[q];
+            nx_vision = is_vision[tok];
+        }
+    };
+    fetch(t);
+    for (int t0 = t - r; t0 < T; t0 += stride, t += stride) {      // uniform trip count: rows past T idle but take part in the DPP steps
+        float v[EPL];
+#pragma unroll
+        for (int q = 0; q < EPL; ++q) v[q] = nx[q];
+        const int vision = nx_vision;
+        const bool live = t < T;
+        fetch(t + stride);
+        float my_val = NEG;                           // lane j keeps the j-th selected logit of its row's token
+        int my_id = 0;
+        for (int sel = 0; sel < k; ++sel) {
+            float best = v[0];
+            int slot = 0;
+#pragma unroll
+            for (int q = 1; q < EPL; ++q)
+                if (v[q] > best) { best = v[q]; slot = q; }
+            const float rmax = row_max(best);
+            const int widx = row_min_i(best == rmax ? j * EPL + slot : 0x7FFFFFFF);
+#pragma unroll
+            for (int q = 0; q < EPL; ++q)
+                if (widx == j * EPL + q) v[q] = NEG;
+            if (j == sel) { my_val = rmax; my_id = widx; }
+        }
+        // gates: softmax over the k selected logits; the first selected one is the row's largest
+        const float top = row_max(j < k ? my_val : NEG);
+        const float e = j < k ? expf(my_val - top) : 0.f;
+        const float sum = row_sum(e);
+        if (live && j < k) {
+            topk_ids[(size_t)t * k + j] = my_id;
+            topk_w[(size_t)t * k + j] = e / sum;
+            atomicAdd(&hist[my_id], 1);
+            if (vision) atomicAdd(&hist[E + my_id], 1);
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < 2 * E; i += blockDim.x) hist_part[(size_t)blockIdx.x * 2 * E + i] = hist[i];
+}
+
 // Adds up the blocks' partial histograms and the per-rank sums (also written to the context's pinned
 // host buffer, which realb_layer_forward reads after one stream synchronisation) (a separate launch: the kernel
 // boundary makes the partials of all XCDs visible).  Thread layout: counter c = tid % CW,
@@ -157,17 +231,35 @@ extern "C" int realb_route_stats(realb_ctx* ctx, const float* logits, const uint
     const int E = c->cfg.E, k = c->cfg.k, D = c->cfg.D;
     int blocks = 0;
     if (T > 0) {
-        blocks = min(ceil_div(T, 16), 2 * c->num_cus);      // 16 waves (tokens in flight) per block, two blocks per CU
         const size_t lds = 2 * (size_t)E * sizeof(int32_t);
-        const int epl = ceil_div(E, 64);
+        if (E <= 128 && E % 16 == 0) {                          // four tokens per wave
+            blocks = min(ceil_div(T, 64), 2 * c->num_cus);      // 16 waves x 4 tokens in flight per block, two blocks per CU
+#define REALB_TOPK_ROWS(EPL)                                                                                      \
+    hipLaunchKernelGGL(topk_hist_rows_kernel<EPL>, dim3(blocks), dim3(1024), lds, s, logits, is_vision, T, E, k, \
+                       topk_ids, topk_w, c->hist_part)
+            switch (E / 16) {
+                case 1: REALB_TOPK_ROWS(1); break;
+                case 2: REALB_TOPK_ROWS(2); break;
+                case 3: REALB_TOPK_ROWS(3); break;
+                case 4: REALB_TOPK_ROWS(4); break;
+                case 5: REALB_TOPK_ROWS(5); break;
+                case 6: REALB_TOPK_ROWS(6); break;
+                case 7: REALB_TOPK_ROWS(7); break;
+                default: REALB_TOPK_ROWS(8); break;
+            }
+#undef REALB_TOPK_ROWS
+        } else {
+            blocks = min(ceil_div(T, 16), 2 * c->num_cus);      // 16 waves (tokens in flight) per block, two blocks per CU
+            const int epl = ceil_div(E, 64);
 #define REALB_TOPK(EPL)                                                                                      \
     hipLaunchKernelGGL(topk_hist_kernel<EPL>, dim3(blocks), dim3(1024), lds, s, logits, is_vision, T, E, k, \
                        topk_ids, topk_w, c->hist_part)
-        if (epl == 1) REALB_TOPK(1);
-        else if (epl == 2) REALB_TOPK(2);
-        else if (epl <= 4) REALB_TOPK(4);
-        else REALB_TOPK(8);
+            if (epl == 1) REALB_TOPK(1);
+            else if (epl == 2) REALB_TOPK(2);
+            else if (epl <= 4) REALB_TOPK(4);
+            else REALB_TOPK(8);
 #undef REALB_TOPK
+        }
     }
     hipLaunchKernelGGL(hist_reduce_kernel, dim3(1), dim3(1024), 2 * (size_t)E * sizeof(int32_t), s, c->hist_part, blocks, E, D,
                        expert_cnt, expert_vis, rank_load, rank_vis, c->stats_host);
