@@ -127,14 +127,21 @@ __device__ __forceinline__ TileInfo decode_tile(const GemmParams& p, int tile, i
     return TileInfo{e, seg_lo + mi * BM, seg_hi, nt * cols_per_tile};
 }
 
+// BF16 outputs larger than what the memory-side cache would keep for the kernel that reads them next are
+// streamed past it with non-temporal stores (uniform per launch).
+__device__ __forceinline__ bool stream_output(const GemmParams& p) {
+    const long long rows = __builtin_amdgcn_readfirstlane(p.offs[p.n_local]);
+    return rows * p.n_out * 2 > (160ll << 20);
+}
+
 // Stores a 32-row x 32-column BF16 tile held as "lane (li, half) owns 16 consecutive columns of row li"
 // (c0 = its first 8 columns, c1 = the next 8).  Writing it as held would touch 32 rows with two
 // separate 16-byte pieces per instruction; a CU sustains only ~16 B/clk of such stores.  Neighbouring
 // lanes therefore swap halves (DPP quad permute), so that one instruction writes the even rows and the
 // next the odd rows, four lanes covering 64 contiguous bytes of a row: 16 rows per instruction, ~3x the
 // store rate measured.  `base` points at column 0 of tile row 0; rows >= rows_left are not written.
-// NT: non-temporal stores -- measured faster on the BF16 path (whose operand stream already overflows
-// the L2) and slower on the FP4 path.
+// NT: non-temporal stores.  They drain faster, but the output then bypasses the memory-side cache, from
+// which the next kernel would otherwise read it back: worth it only for outputs too large to stay there.
 template <bool NT>
 __device__ __forceinline__ void store_tile_rows(uint8_t* base, size_t row_pitch, int lane, int rows_left,
                                                 const u32x4_t& c0, const u32x4_t& c1) {
@@ -166,7 +173,7 @@ __device__ __forceinline__ void store_tile_rows(uint8_t* base, size_t row_pitch,
 // Epilogue, straight from registers.  acc[mt][t][r] belongs to activation row wm*128 + mt*32 + li
 // of the tile and to column 16*half + r of the wave's t-th 32-column tile.  rows_valid = rows of
 // this tile that exist (may exceed the tile height).
-template <bool FP4, bool GATEUP, int WN>
+template <bool FP4, bool GATEUP, int WN, bool NT>
 __device__ __forceinline__ void epilogue(const GemmParams& p, v16f_t (&acc)[4][WN], int row0, int rows_valid, int n0,
                                          int wm, int wn, int li, int half) {
     const int lane = half * 32 + li;
@@ -201,8 +208,8 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, v16f_t (&acc)[4][W
                     }
                 } else {
                     const int tile_row0 = wm * 128 + mt * 32;
-                    store_tile_rows<true>(p.out + ((size_t)(row0 + tile_row0) * p.n_out + ctile) * 2, (size_t)p.n_out * 2, lane,
-                                    rows_valid - tile_row0, u32x4_t{hb[0], hb[1], hb[2], hb[3]}, u32x4_t{hb[4], hb[5], hb[6], hb[7]});
+                    store_tile_rows<NT>(p.out + ((size_t)(row0 + tile_row0) * p.n_out + ctile) * 2, (size_t)p.n_out * 2, lane,
+                                        rows_valid - tile_row0, u32x4_t{hb[0], hb[1], hb[2], hb[3]}, u32x4_t{hb[4], hb[5], hb[6], hb[7]});
                 }
             }
         }
@@ -213,7 +220,7 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, v16f_t (&acc)[4][W
 #pragma unroll
             for (int t = 0; t < WN; ++t) {
                 const int col0 = n0 + wn * WN * 32 + t * 32;
-                store_tile_rows<!FP4>(p.out + ((size_t)(row0 + tile_row0) * p.n_out + col0) * 2, (size_t)p.n_out * 2, lane,
+                store_tile_rows<NT>(p.out + ((size_t)(row0 + tile_row0) * p.n_out + col0) * 2, (size_t)p.n_out * 2, lane,
                                 rows_valid - tile_row0,
                                 u32x4_t{pack_bf16x2(acc[mt][t][0], acc[mt][t][1]), pack_bf16x2(acc[mt][t][2], acc[mt][t][3]),
                                         pack_bf16x2(acc[mt][t][4], acc[mt][t][5]), pack_bf16x2(acc[mt][t][6], acc[mt][t][7])},
@@ -249,6 +256,7 @@ __global__ void __launch_bounds__(128 * WGN, MINB) ffn_gemm_kernel(const GemmPar
     const int tile_hi = min(total, ((int)(blockIdx.x & 7) + 1) * per_xcd);
     int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (tile >= tile_hi) return;
+    const bool nt_out = stream_output(p);
 
     const int I_up = p.w_rows >> 1;                       // gate/up: offset of the up rows
     const size_t rowbytes = FP4 ? (size_t)(p.K >> 1) : (size_t)p.K * 2;
@@ -406,7 +414,8 @@ __global__ void __launch_bounds__(128 * WGN, MINB) ffn_gemm_kernel(const GemmPar
         }
 
         // ---- epilogue, straight from registers
-        epilogue<FP4, GATEUP, WN>(p, acc, cur.row0, cur.seg_hi - cur.row0, cur.n0, wm, wn, li, half);
+        if (nt_out) epilogue<FP4, GATEUP, WN, true>(p, acc, cur.row0, cur.seg_hi - cur.row0, cur.n0, wm, wn, li, half);
+        else epilogue<FP4, GATEUP, WN, false>(p, acc, cur.row0, cur.seg_hi - cur.row0, cur.n0, wm, wn, li, half);
         if (!more) break;
     }
 }
@@ -499,6 +508,7 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
     int tile = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     if (tile >= tile_hi) return;
 
+    const bool nt_out = stream_output(p);
     const int I_up = p.w_rows >> 1;
     const uint32_t rowbytes = FP4 ? (uint32_t)(p.K >> 1) : (uint32_t)p.K * 2;
     const int nks = (int)((rowbytes + KB - 1) / KB);
@@ -699,7 +709,8 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
 
         ++ks;
         if (last) {
-            epilogue<FP4, GATEUP, 2>(p, acc, cur_row0, cur_rows, cur_n0, wm, wn, li, half);
+            if (nt_out) epilogue<FP4, GATEUP, 2, true>(p, acc, cur_row0, cur_rows, cur_n0, wm, wn, li, half);
+            else epilogue<FP4, GATEUP, 2, false>(p, acc, cur_row0, cur_rows, cur_n0, wm, wn, li, half);
             tile += nslots;
             if (tile >= tile_hi) break;
 #pragma unroll
