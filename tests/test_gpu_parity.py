@@ -130,6 +130,35 @@ def test_route_stats(R, case):
     assert int(b.expert_cnt.sum()) == c.T * c.k                       # conservation on the device result
 
 
+@pytest.mark.parametrize("E,k,D", [(16, 2, 2), (48, 4, 3), (80, 8, 5), (112, 16, 7), (128, 8, 8), (8, 2, 1), (24, 3, 2), (256, 8, 8), (512, 16, 8)])
+def test_route_stats_expert_counts_and_ties(R, E, k, D):
+    """Every instantiation of the two top-k kernels (a DPP row per token for E <= 128 and a multiple of 16,
+    a wave per token otherwise), with ties planted: equal logits must resolve to the lower expert index, and
+    a T that leaves the last wave's rows partly empty."""
+    from paper_2604_19503_amd.binding import default_config
+    from oracle import router as orouter
+    T = 1003
+    rng = np.random.default_rng(E * 100 + k)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    logits[::3] = np.round(logits[::3] * 2) / 2                   # many exact ties
+    logits[5] = 0.25                                              # a token whose logits are all equal
+    logits[6, : E // 2] = 1.5                                     # half the experts tied at the top
+    isv_np = (rng.random(T) < 0.6).astype(np.uint8)
+    _say(f"route_stats E={E} k={k} D={D}")
+    rcfg = default_config(T, E, k, D, 128, 128)
+    ctx = R.Context(rcfg)
+    b = R.LayerBuffers(rcfg, T)
+    ctx.route_stats(torch.from_numpy(logits).cuda(), torch.from_numpy(isv_np).cuda(), b)
+    _sync()
+    ids, w = orouter.topk_route(logits, k)
+    cnt, vis, load, lvis = orouter.route_counts(ids, isv_np, E, D)
+    assert same(b.topk_ids.cpu().numpy(), ids)
+    assert np.allclose(b.topk_w.cpu().numpy().astype(np.float64), w, rtol=GATE_W_RTOL, atol=1e-9)
+    assert same(b.expert_cnt.cpu().numpy(), cnt) and same(b.expert_vis.cpu().numpy(), vis)
+    assert same(b.rank_load.cpu().numpy(), load) and same(b.rank_vis.cpu().numpy(), lvis)
+    ctx.close()
+
+
 def test_select_precision_from_device_stats(R, case):
     c, b = case.cfg, case.buf
     case.ctx.route_stats(case.logits, case.is_vision, b)
