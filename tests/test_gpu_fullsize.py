@@ -22,8 +22,8 @@ BF16_TOL = 1e-2
 
 def _say(msg):
     print(f"[gpu-fullsize] {msg}", flush=True)
-    out_dir = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(out_dir):
+    out_dir = os.environ.get("REALB_TEST_LOG_DIR", "")     # optional: also append the progress lines to a file there
+    if out_dir and os.path.isdir(out_dir):
         with open(os.path.join(out_dir, "parity_metrics.log"), "a") as f:
             f.write("[fullsize] " + msg + "\n")
 

@@ -24,8 +24,8 @@ MAX_FLIP_FRACTION = 1e-3
 def _say(msg):
     print(f"[gpu-parity] {msg}", flush=True)
     sys.stdout.flush()
-    out_dir = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
-    if os.path.isdir(out_dir):
+    out_dir = os.environ.get("REALB_TEST_LOG_DIR", "")     # optional: also append the progress lines to a file there
+    if out_dir and os.path.isdir(out_dir):
         with open(os.path.join(out_dir, "parity_metrics.log"), "a") as f:
             f.write(msg + "\n")
 
