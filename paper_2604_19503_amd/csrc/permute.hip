@@ -31,35 +31,49 @@ __global__ void __launch_bounds__(256) perm_count_kernel(const int32_t* __restri
             const unsigned long long m = __ballot(le[i] == e);
             if (lane == e) cnt += __popcll(m);
         }
-    if (lane < n_local) wave_cnt[chunk * n_local + lane] = cnt;
+    if (lane < n_local) wave_cnt[(size_t)lane * n_chunks + chunk] = cnt;     // expert-major: the scan reads a column contiguously
 }
 
-__device__ __forceinline__ int wave_inclusive_scan(int v, int lane) {
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        int o = __shfl_up(v, d);
-        if (lane >= d) v += o;
-    }
+// Inclusive prefix sum over the 64 lanes with DPP only: four shifts inside each row of 16 lanes, then the
+// last lane of row 0 / row 2 is added to the following row, then lane 31 to the upper half.
+__device__ __forceinline__ int wave_inclusive_scan(int v, int /*lane*/) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, false);     // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, false);     // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, false);     // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, false);     // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);     // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);     // row_bcast:31 into rows 2 and 3
     return v;
 }
 
 // Phase 2 (one block): per expert, exclusive scan of the chunk counts in chunk
 // order (in place: counts become the chunk's first rank within the expert), then
-// the exclusive scan over experts gives expert_offsets.
+// the exclusive scan over experts gives expert_offsets.  A wave takes an expert and walks its
+// column 64 chunks at a time; the loads of up to 16 such steps are issued together (one memory
+// latency instead of one per step), then the steps are scanned in order with a running carry.
 __global__ void __launch_bounds__(1024) perm_scan_kernel(int32_t* __restrict__ wave_cnt, int n_chunks, int n_local,
                                                          int32_t* __restrict__ expert_offsets) {
+    constexpr int BATCH = 16;
     __shared__ int totals[64];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int n_waves = blockDim.x >> 6;
     for (int e = wave; e < n_local; e += n_waves) {
         int carry = 0;
-        for (int c0 = 0; c0 < n_chunks; c0 += 64) {
-            const int c = c0 + lane;
-            const int v = (c < n_chunks) ? wave_cnt[c * n_local + e] : 0;
-            const int incl = wave_inclusive_scan(v, lane);
-            if (c < n_chunks) wave_cnt[c * n_local + e] = carry + incl - v;
-            carry += __shfl(incl, 63);
+        for (int c0 = 0; c0 < n_chunks; c0 += 64 * BATCH) {
+            int v[BATCH];
+#pragma unroll
+            for (int i = 0; i < BATCH; ++i) {
+                const int c = c0 + i * 64 + lane;
+                v[i] = (c < n_chunks) ? wave_cnt[(size_t)e * n_chunks + c] : 0;
+            }
+#pragma unroll
+            for (int i = 0; i < BATCH; ++i) {
+                const int c = c0 + i * 64 + lane;
+                const int incl = wave_inclusive_scan(v[i], lane);
+                if (c < n_chunks) wave_cnt[(size_t)e * n_chunks + c] = carry + incl - v[i];
+                carry += __builtin_amdgcn_readlane(incl, 63);
+            }
         }
         if (lane == 0) totals[e] = carry;
     }
@@ -87,7 +101,7 @@ __global__ void __launch_bounds__(256) perm_rank_kernel(const int32_t* __restric
         const int a = begin + i * 64 + lane;
         le[i] = (a < A) ? topk_ids[a] - lo : -1;
     }
-    int running = (lane < n_local) ? expert_offsets[lane] + wave_cnt[chunk * n_local + lane] : 0;
+    int running = (lane < n_local) ? expert_offsets[lane] + wave_cnt[(size_t)lane * n_chunks + chunk] : 0;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
 #pragma unroll
     for (int i = 0; i < kIters; ++i) {
@@ -127,10 +141,14 @@ __global__ void __launch_bounds__(256) perm_gather_kernel(const u32x4_t* __restr
             const int c = u * 64 + lane;
             v[u] = c < chunks ? src[c] : u32x4_t{0, 0, 0, 0};
         }
-        uint32_t codes[CPL], byte[CPL];
+        uint32_t codes[CPL], byte[CPL], word[CPL];
         if (FP4) {
 #pragma unroll
-            for (int u = 0; u < CPL; ++u) codes[u] = encode_block_quad(v[u], &byte[u]);
+            for (int u = 0; u < CPL; ++u) {
+                codes[u] = encode_block_quad(v[u], &byte[u]);
+                word[u] = byte[u] | ((uint32_t)__shfl_down((int)byte[u], 4) << 8) | ((uint32_t)__shfl_down((int)byte[u], 8) << 16) |
+                          ((uint32_t)__shfl_down((int)byte[u], 12) << 24);
+            }
         }
         for (int j = 0; j < k; ++j) {
             const int r = __builtin_amdgcn_readlane(my_row, j);
@@ -141,7 +159,10 @@ __global__ void __launch_bounds__(256) perm_gather_kernel(const u32x4_t* __restr
                 if (c < chunks) {
                     if (FP4) {
                         x_q[(size_t)r * chunks + c] = codes[u];
-                        if ((lane & 3) == 0) x_s[scale_byte_offset(r, c >> 2, chunks >> 4)] = (uint8_t)byte[u];
+                        // the four scales of a 128-element K-step are one dword of the tiled tensor: lane 16m
+                        // stores the dword packed from lanes 16m, 16m+4, 16m+8, 16m+12 (chunks is a multiple of 16)
+                        if ((lane & 15) == 0)
+                            *reinterpret_cast<uint32_t*>(x_s + scale_byte_offset(r, c >> 2, chunks >> 4)) = word[u];
                     } else {
                         x_perm[(size_t)r * chunks + c] = v[u];
                     }

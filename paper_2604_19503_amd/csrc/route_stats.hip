@@ -199,8 +199,15 @@ __global__ void __launch_bounds__(1024) hist_reduce_kernel(const int32_t* __rest
     const int c = threadIdx.x % cw, slice = threadIdx.x / cw;
     if (c < C2 && slice < n_slices) {
         int sum = 0;
-#pragma unroll 8
-        for (int b = slice; b < n_part; b += n_slices) sum += hist_part[(size_t)b * C2 + c];
+        int b = slice;
+        for (; b + 31 * n_slices < n_part; b += 32 * n_slices) {       // 32 independent loads in flight per thread
+            int v[32];
+#pragma unroll
+            for (int i = 0; i < 32; ++i) v[i] = hist_part[(size_t)(b + i * n_slices) * C2 + c];
+#pragma unroll
+            for (int i = 0; i < 32; ++i) sum += v[i];
+        }
+        for (; b < n_part; b += n_slices) sum += hist_part[(size_t)b * C2 + c];
         if (sum) atomicAdd(&tot[c], sum);
     }
     __syncthreads();
