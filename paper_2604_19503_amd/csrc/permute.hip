@@ -129,9 +129,20 @@ __global__ void __launch_bounds__(256) perm_gather_kernel(const u32x4_t* __restr
                                                           uint32_t* __restrict__ x_q, uint8_t* __restrict__ x_s) {
     const int lane = threadIdx.x & 63;
     const int chunks = H >> 3;                             // 16-B chunks per row, multiple of 16
-    const int wave_global = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
-    const int n_waves = gridDim.x * (blockDim.x >> 6);
-    for (int t = wave_global; t < T; t += n_waves) {
+    // A block takes a contiguous range of tokens: the rows of one 32-row group of an expert come from
+    // tokens close together, so their scale words (which share 128-byte lines in the tiled scale tensor)
+    // are written through the same L2 and leave it as whole lines.
+    // Blocks b, b+8, .. share an XCD: each XCD takes one contiguous eighth of the tokens, its blocks
+    // contiguous pieces of it.
+    // (BF16 rows are whole lines anyway; there the strided assignment of tokens to blocks measured faster.)
+    const int per_xcd = (T + 7) >> 3, nb = max((int)gridDim.x >> 3, 1);
+    const int x_lo = (int)(blockIdx.x & 7) * per_xcd, x_hi = min(T, x_lo + per_xcd);
+    const int per_block = (per_xcd + nb - 1) / nb;
+    const int t_lo = FP4 ? x_lo + (int)(blockIdx.x >> 3) * per_block + (int)(threadIdx.x >> 6)
+                         : (int)(blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6));
+    const int t_end = FP4 ? min(x_hi, x_lo + ((int)(blockIdx.x >> 3) + 1) * per_block) : T;
+    const int t_step = FP4 ? (int)(blockDim.x >> 6) : (int)(gridDim.x * (blockDim.x >> 6));
+    for (int t = t_lo; t < t_end; t += t_step) {
         const int my_row = lane < k ? assign_to_row[(size_t)t * k + lane] : -1;
         if (__ballot(my_row >= 0) == 0ull) continue;       // no local expert for this token
         const u32x4_t* src = x + (size_t)t * chunks;
@@ -227,7 +238,7 @@ int permute_gather(Ctx* c, const void* x, const int32_t* assign_to_row, int T, i
     REALB_REQUIRE(x && assign_to_row, REALB_EINVAL, "NULL argument");
     REALB_REQUIRE(prec == REALB_BF16 ? x_perm != nullptr : (x_q && x_s), REALB_EINVAL, "NULL row buffer");
     const int k = c->cfg.k, H = c->cfg.H;
-    const int blocks = T < 4 ? 1 : (T / 4 < 256 * 16 ? T / 4 : 256 * 16);
+    const int blocks = 8 * (T < 32 ? 1 : (T / 32 < 512 ? T / 32 : 512));      // a multiple of 8 (XCDs), 4 waves each
     if (prec == REALB_FP4) launch_gather<true>(blocks, s, x, assign_to_row, T, k, H, nullptr, x_q, x_s);
     else launch_gather<false>(blocks, s, x, assign_to_row, T, k, H, x_perm, nullptr, nullptr);
     REALB_HIP(hipGetLastError());
