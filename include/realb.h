@@ -222,6 +222,9 @@ typedef struct {
     int32_t prec_host[64]; double ib_global; double M_after;
 } realb_layer_io;
 
+/* (On the BF16 path realb_layer_forward / realb_rank_forward may leave x_perm unwritten: where the
+ * gate/up GEMM can fetch its rows from x through row_to_assign, the permuted copy is not materialised.) */
+
 /* Runs the whole path for one rank on `stream`: route_stats -> select_precision
  * (host decision, one stream sync) -> [FP4 only: quantize_experts_fp4, on the
  * context's side stream when io->overlap, concurrent with] permute ->

@@ -34,6 +34,8 @@ int select_precision_pinned(Ctx* c, int T, int force, int32_t* prec_host, double
                             hipEvent_t ready);
 int permute_indices(Ctx* c, const int32_t* topk_ids, int T, int rank, long long max_rows, int32_t* expert_offsets,
                     int32_t* row_to_assign, int32_t* assign_to_row, hipStream_t s);
+int launch_gate_up_bf16_gather(Ctx* c, const int32_t* expert_offsets, int n_local, long long max_rows, const void* x, int T,
+                               const int32_t* row_to_assign, const void* w13, void* h_mid, hipStream_t s);
 int permute_gather(Ctx* c, const void* x, const int32_t* assign_to_row, int T, int prec, void* x_perm, uint8_t* x_q,
                    uint8_t* x_s, hipStream_t s);
 int hip_fail(hipError_t e, const char* what);

@@ -70,6 +70,8 @@ struct GemmParams {
     int w_rows;              // weight rows per expert (2I or H)
     int n_out;               // output columns (I or H)
     int n_tiles_n;           // column tiles (I/GC or H/BNW)
+    const int32_t* row_src;  // gathering gate/up GEMM only: row_to_assign; row r's activations are A[row_src[r] / src_div]
+    int src_div;             //                              (experts per token)
 };
 
 // acc += W_tile (A operand, 32 weight rows) x X_tile^T (B operand, 32 activation rows)
@@ -465,7 +467,9 @@ __device__ __forceinline__ void lds_dma4(const uint32_t* g, uint8_t* l) {
                                      (__attribute__((address_space(3))) void*)l, 4, 0, 0);
 }
 
-template <bool FP4, bool GATEUP>
+// GATHER (BF16 gate/up only): the activation rows are fetched straight from the token matrix through
+// row_to_assign, so the permuted copy of the activations never has to be written.
+template <bool FP4, bool GATEUP, bool GATHER = false>
 __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p) {
     using namespace t256;
     constexpr int COLS = GATEUP ? 128 : 256;   // output columns per block
@@ -540,6 +544,7 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
         for (int q = 0; q < 2; ++q) b_voff[q] = (uint32_t)w_tile_row<GATEUP, 128>(br0, 0, I_up) * rowbytes + part16(q);
     }
     int a_last = 0;                                       // scalar: last existing row of the tile being fetched
+    uint32_t a_goff[GATHER ? 4 : 1];                      // GATHER: byte offset of this lane's source row, per instruction
     const int srow = wave * 32 + (lane >> 1), swhich = lane & 1;
     int sa_idx = 0, sb_idx = 0;                           // FP4: dword index of this lane's scale word, K-step 0
     const uint8_t* a_tile = nullptr;                      // scalar: first activation row / weight row of the tile being fetched
@@ -549,9 +554,16 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
     auto setup_src = [&](const TileInfo& t) __attribute__((always_inline)) {
         const int row0 = __builtin_amdgcn_readfirstlane(t.row0), rows = __builtin_amdgcn_readfirstlane(t.seg_hi - t.row0);
         const int e = __builtin_amdgcn_readfirstlane(t.e), n0 = __builtin_amdgcn_readfirstlane(t.n0);
-        a_tile = p.A + (size_t)row0 * rowbytes;
+        a_tile = GATHER ? p.A : p.A + (size_t)row0 * rowbytes;
         b_tile = p.W + ((size_t)e * p.w_rows + n0) * rowbytes;
         a_last = rows - 1;
+        if constexpr (GATHER) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int r = row0 + min(wave * 32 + j * 8 + prow, rows - 1);
+                a_goff[j] = (uint32_t)(p.row_src[r] / p.src_div) * rowbytes + part16(j & 1);
+            }
+        }
         if constexpr (FP4) {
             const int gr = row0 + min(srow, rows - 1);
             sa_idx = ((gr >> 5) * kd) * 32 + (gr & 31);
@@ -576,7 +588,9 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
             const uint32_t koff = (uint32_t)(k * KB) - (halfstep ? (uint32_t)(((lane << 4) ^ ((j & 1) << 6)) & 64) : 0u);
             uint8_t* l = smem + dstg * STAGE + (wave * 4 + j) * 1024;
             if (op < 6) {
-                const uint32_t v = (uint32_t)min(wave * 32 + j * 8 + prow, a_last) * rowbytes + part16(j & 1);   // rows past the segment: its last row again
+                uint32_t v;
+                if constexpr (GATHER) v = a_goff[j];
+                else v = (uint32_t)min(wave * 32 + j * 8 + prow, a_last) * rowbytes + part16(j & 1);   // rows past the segment: its last row again
                 lds_dma16(a_tile + (v + koff), l);
             } else {
                 lds_dma16(b_tile + (size_t)(j * 4) * rowbytes + (b_voff[j & 1] + koff), l + REGION_W);
@@ -727,13 +741,13 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // no transfer may still be writing this block's LDS when it ends
 }
 
-template <bool FP4, bool GATEUP>
+template <bool FP4, bool GATEUP, bool GATHER = false>
 static int launch_gemm256(GemmParams p, long long max_rows, int num_cus, hipStream_t s) {
     p.n_tiles_n = p.n_out / (GATEUP ? 128 : 256);
     const size_t lds = t256::LDS_BYTES;
     static bool attr_done = false;
     if (!attr_done) {
-        REALB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_gemm256_kernel<FP4, GATEUP>),
+        REALB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_gemm256_kernel<FP4, GATEUP, GATHER>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
         attr_done = true;
     }
@@ -741,7 +755,7 @@ static int launch_gemm256(GemmParams p, long long max_rows, int num_cus, hipStre
     const long long total_max = m_tiles_max * p.n_tiles_n;
     const long long slots = 8ll * (((long long)num_cus + 7) / 8);          // one persistent block per CU, multiple of 8 (XCDs)
     const long long grid = total_max < slots ? 8 * ((total_max + 7) / 8) : slots;
-    hipLaunchKernelGGL((ffn_gemm256_kernel<FP4, GATEUP>), dim3((unsigned)grid), dim3(512), lds, s, p);
+    hipLaunchKernelGGL((ffn_gemm256_kernel<FP4, GATEUP, GATHER>), dim3((unsigned)grid), dim3(512), lds, s, p);
     REALB_HIP(hipGetLastError());
     return REALB_OK;
 }
@@ -785,6 +799,18 @@ static int launch_gemm(const GemmParams& p, long long max_rows, int num_cus, hip
     return launch_gemm_geo<FP4, GATEUP, 2, 2, 2>(p, max_rows, num_cus, s);
 }
 
+// BF16 gate/up GEMM that gathers its activation rows from the token matrix x [T,H] through row_to_assign
+// (the permutation's gather fused into the GEMM's loads).  Returns REALB_ESHAPE if this shape or the
+// selected kernel cannot do it; the caller then materialises the permuted rows and uses the plain GEMM.
+int launch_gate_up_bf16_gather(Ctx* c, const int32_t* expert_offsets, int n_local, long long max_rows, const void* x, int T,
+                               const int32_t* row_to_assign, const void* w13, void* h_mid, hipStream_t s) {
+    const int H = c->cfg.H, I = c->cfg.I;
+    if (!(g_tile == 0 || g_tile == 16) || I % 128 != 0 || (long long)T * H * 2 >= (1ll << 32)) return REALB_ESHAPE;
+    GemmParams g{(const uint8_t*)x, nullptr, (const uint8_t*)w13, nullptr, (uint8_t*)h_mid, nullptr, expert_offsets, n_local,
+                 H, 2 * I, I, 0, row_to_assign, c->cfg.k};
+    return launch_gemm256<false, true, true>(g, max_rows, c->num_cus, s);
+}
+
 }  // namespace realb
 
 using namespace realb;
@@ -810,8 +836,8 @@ static int ffn_stages(realb_ctx* ctx, int prec, int stages, const int32_t* exper
                   "NULL scale tensor on the FP4 path");
     const int H = c->cfg.H, I = c->cfg.I;
     hipStream_t s = as_stream(stream);
-    GemmParams g1{(const uint8_t*)x, x_s, (const uint8_t*)w13, w13_s, (uint8_t*)h_mid, h_s, expert_offsets, n_local, H, 2 * I, I, 0};
-    GemmParams g2{(const uint8_t*)h_mid, h_s, (const uint8_t*)w2, w2_s, (uint8_t*)y_rows, nullptr, expert_offsets, n_local, I, H, H, 0};
+    GemmParams g1{(const uint8_t*)x, x_s, (const uint8_t*)w13, w13_s, (uint8_t*)h_mid, h_s, expert_offsets, n_local, H, 2 * I, I, 0, nullptr, 1};
+    GemmParams g2{(const uint8_t*)h_mid, h_s, (const uint8_t*)w2, w2_s, (uint8_t*)y_rows, nullptr, expert_offsets, n_local, I, H, H, 0, nullptr, 1};
     int rc = REALB_OK;
     if (prec == REALB_FP4) {
         if (s1) rc = launch_gemm<true, true>(g1, max_rows, c->num_cus, s);

@@ -110,6 +110,10 @@ def test_full_size_layer(name):
             _say(f"{name}: fp4 sampled rows: staged rel fro max {staged:.3e}, end-to-end max {full:.3e}")
             assert staged <= FP4_TOL and full <= 3 * FP4_TOL
         else:
+            # the layer call fetches the BF16 rows through row_to_assign inside the gate/up GEMM and need not
+            # materialise x_perm; the permutation entry point itself is checked here
+            ctx.permute(x, buf, cfg.rank, R.BF16)
+            torch.cuda.synchronize()
             assert np.array_equal(R.bits_from_bf16(buf.x_perm[:Rr]), inp["x"][tok])
             for e, rows in samples:
                 _, y = offn.ffn_bf16(inp["x"][tok[rows]], inp["w13"][e:e + 1], inp["w2"][e:e + 1], [0, len(rows)])
