@@ -54,8 +54,8 @@ PEAK_HBM_GBS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=300, help="untimed steps first; the clocks need about 100 ms of load to settle")
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "gate-sweep", "policy-ablation", "format-gap"],
                     help="c2 (default) is the headline line; c4 = 8-rank imbalance simulation, c5 = 48-layer overlap stress, "
                          "gate-sweep = FP4 vs BF16 layer time over the batch size (locates the LB gate), "
@@ -65,10 +65,10 @@ def parse():
     ap.add_argument("--iterations", type=int, default=100, help="trace length of the policy ablation")
     ap.add_argument("--precision", default="fp4", choices=["fp4", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--encode-mode", default="main", choices=["speculative", "side", "main"],
-                    help="where the FP4 weight encoding runs: main stream after the decision (default: measured fastest on the "
-                         "headline workload), side stream before routing, or side stream after the decision (under the permutation); "
-                         "the step is timed in all three and reported under extra")
+    ap.add_argument("--encode-mode", default="speculative", choices=["speculative", "side", "main"],
+                    help="where the FP4 weight encoding runs: side stream before routing (default: measured fastest), main stream "
+                         "after the decision, or side stream after the decision (under the permutation); the step is timed in "
+                         "all three and reported under extra")
     ap.add_argument("--gemm-tile", type=int, default=0, choices=[0, 2, 8, 16], help="grouped-GEMM block tile selector (0 = automatic)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy (untimed) so that a counter run can scale FETCH_SIZE / WRITE_SIZE")

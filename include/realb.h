@@ -222,8 +222,11 @@ typedef struct {
     int32_t prec_host[64]; double ib_global; double M_after;
 } realb_layer_io;
 
-/* (On the BF16 path realb_layer_forward / realb_rank_forward may leave x_perm unwritten: where the
- * gate/up GEMM can fetch its rows from x through row_to_assign, the permuted copy is not materialised.) */
+/* (realb_layer_forward / realb_rank_forward fuse the permutation's gather into the gate/up GEMM where
+ * that GEMM can fetch its rows through row_to_assign: on the BF16 path x_perm is then left unwritten, and
+ * on the FP4 path x_q / x_s hold one encoded row per TOKEN that has a local expert -- row index = token
+ * index, scales tiled by token index -- instead of one per permuted row.  realb_permute itself always
+ * produces the permuted rows described above.) */
 
 /* Runs the whole path for one rank on `stream`: route_stats -> select_precision
  * (host decision, one stream sync) -> [FP4 only: quantize_experts_fp4, on the

@@ -36,8 +36,12 @@ int permute_indices(Ctx* c, const int32_t* topk_ids, int T, int rank, long long 
                     int32_t* row_to_assign, int32_t* assign_to_row, hipStream_t s);
 int launch_gate_up_bf16_gather(Ctx* c, const int32_t* expert_offsets, int n_local, long long max_rows, const void* x, int T,
                                const int32_t* row_to_assign, const void* w13, void* h_mid, hipStream_t s);
+bool gate_up_gather_supported(const Ctx* c, int T, bool fp4);
+int launch_gate_up_fp4_gather(Ctx* c, const int32_t* expert_offsets, int n_local, long long max_rows, const uint8_t* x_q,
+                              const uint8_t* x_s, int T, const int32_t* row_to_assign, const uint8_t* w13_q,
+                              const uint8_t* w13_s, uint8_t* h_q, uint8_t* h_s, hipStream_t s);
 int permute_gather(Ctx* c, const void* x, const int32_t* assign_to_row, int T, int prec, void* x_perm, uint8_t* x_q,
-                   uint8_t* x_s, hipStream_t s);
+                   uint8_t* x_s, hipStream_t s, int token_major);
 int hip_fail(hipError_t e, const char* what);
 
 #define REALB_HIP(call)                                                        \

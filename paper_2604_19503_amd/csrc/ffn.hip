@@ -467,8 +467,8 @@ __device__ __forceinline__ void lds_dma4(const uint32_t* g, uint8_t* l) {
                                      (__attribute__((address_space(3))) void*)l, 4, 0, 0);
 }
 
-// GATHER (BF16 gate/up only): the activation rows are fetched straight from the token matrix through
-// row_to_assign, so the permuted copy of the activations never has to be written.
+// GATHER (gate/up only): the activation rows are fetched straight from a token-indexed matrix (x itself,
+// or the tokens' FP4 codes and scales) through row_to_assign, so no permuted copy has to be written.
 template <bool FP4, bool GATEUP, bool GATHER = false>
 __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p) {
     using namespace t256;
@@ -565,7 +565,8 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
             }
         }
         if constexpr (FP4) {
-            const int gr = row0 + min(srow, rows - 1);
+            int gr = row0 + min(srow, rows - 1);
+            if constexpr (GATHER) gr = p.row_src[gr] / p.src_div;      // the token that holds this row's codes and scales
             sa_idx = ((gr >> 5) * kd) * 32 + (gr & 31);
             const int br = (srow & ~31) | w_row_of_lane(srow & 31);
             const int wr = e * p.w_rows + w_tile_row<GATEUP, 128>(br, n0, I_up);
@@ -799,16 +800,32 @@ static int launch_gemm(const GemmParams& p, long long max_rows, int num_cus, hip
     return launch_gemm_geo<FP4, GATEUP, 2, 2, 2>(p, max_rows, num_cus, s);
 }
 
+// Whether the gathering gate/up GEMM below applies (kernel selection, 32-bit row offsets).
+bool gate_up_gather_supported(const Ctx* c, int T, bool fp4) {
+    const long long bytes = (long long)T * c->cfg.H * (fp4 ? 1 : 4) / 2;
+    return (g_tile == 0 || g_tile == 16) && c->cfg.I % 128 == 0 && T > 0 && bytes < (1ll << 32);
+}
+
 // BF16 gate/up GEMM that gathers its activation rows from the token matrix x [T,H] through row_to_assign
 // (the permutation's gather fused into the GEMM's loads).  Returns REALB_ESHAPE if this shape or the
 // selected kernel cannot do it; the caller then materialises the permuted rows and uses the plain GEMM.
 int launch_gate_up_bf16_gather(Ctx* c, const int32_t* expert_offsets, int n_local, long long max_rows, const void* x, int T,
                                const int32_t* row_to_assign, const void* w13, void* h_mid, hipStream_t s) {
     const int H = c->cfg.H, I = c->cfg.I;
-    if (!(g_tile == 0 || g_tile == 16) || I % 128 != 0 || (long long)T * H * 2 >= (1ll << 32)) return REALB_ESHAPE;
+    if (!gate_up_gather_supported(c, T, false)) return REALB_ESHAPE;
     GemmParams g{(const uint8_t*)x, nullptr, (const uint8_t*)w13, nullptr, (uint8_t*)h_mid, nullptr, expert_offsets, n_local,
                  H, 2 * I, I, 0, row_to_assign, c->cfg.k};
     return launch_gemm256<false, true, true>(g, max_rows, c->num_cus, s);
+}
+
+// The same for the FP4 path: x_q / x_s hold one encoded row per TOKEN (row index = token index).
+int launch_gate_up_fp4_gather(Ctx* c, const int32_t* expert_offsets, int n_local, long long max_rows, const uint8_t* x_q,
+                              const uint8_t* x_s, int T, const int32_t* row_to_assign, const uint8_t* w13_q,
+                              const uint8_t* w13_s, uint8_t* h_q, uint8_t* h_s, hipStream_t s) {
+    const int H = c->cfg.H, I = c->cfg.I;
+    if (!gate_up_gather_supported(c, T, true)) return REALB_ESHAPE;
+    GemmParams g{x_q, x_s, w13_q, w13_s, h_q, h_s, expert_offsets, n_local, H, 2 * I, I, 0, row_to_assign, c->cfg.k};
+    return launch_gemm256<true, true, true>(g, max_rows, c->num_cus, s);
 }
 
 }  // namespace realb

@@ -36,29 +36,35 @@ static int rank_forward_impl(realb_ctx* ctx, realb_layer_io* io, int prec, void*
                              io->assign_to_row, s);
         if (rc != REALB_OK) return rc;
     }
-    // BF16: the gate/up GEMM can fetch its rows from x through row_to_assign, so the permuted copy of the
-    // activations (x_perm) is neither written nor read; only where that kernel does not apply is it materialised.
-    bool gathered = false;
-    if (!fp4 && io->T > 0 && io->x && io->w13 && io->h_mid && io->row_to_assign) {
-        rc = launch_gate_up_bf16_gather(c, io->expert_offsets, c->n_local, io->max_rows, io->x, io->T, io->row_to_assign,
-                                        io->w13, io->h_mid, s);
-        if (rc == REALB_OK) gathered = true;
-        else if (rc != REALB_ESHAPE) return rc;
-    }
-    if (!gathered) {
-        rc = permute_gather(c, io->x, io->assign_to_row, io->T, prec, io->x_perm, io->x_q, io->x_s, s);
+    // Where the gate/up GEMM can fetch its rows through row_to_assign, the permuted copy of the activations is
+    // not materialised: BF16 rows come straight from x; FP4 rows from codes and scales written once per TOKEN.
+    const bool gather = io->row_to_assign && io->x && gate_up_gather_supported(c, io->T, fp4);
+    if (fp4 || !gather) {
+        rc = permute_gather(c, io->x, io->assign_to_row, io->T, prec, io->x_perm, io->x_q, io->x_s, s, gather ? 1 : 0);
         if (rc != REALB_OK) return rc;
     }
     if (fp4 && side) REALB_HIP(hipStreamWaitEvent(s, c->ev_join, 0));
-    if (fp4)
+    if (gather) {
+        REALB_REQUIRE(io->h_mid && io->w2 && io->y_rows, REALB_EINVAL, "NULL argument");
+        if (fp4) {
+            REALB_REQUIRE(io->x_q && io->x_s && io->h_s, REALB_EINVAL, "NULL argument");
+            rc = launch_gate_up_fp4_gather(c, io->expert_offsets, c->n_local, io->max_rows, io->x_q, io->x_s, io->T,
+                                           io->row_to_assign, io->w13_q, io->w13_s, (uint8_t*)io->h_mid, io->h_s, s);
+        } else {
+            REALB_REQUIRE(io->w13 != nullptr, REALB_EINVAL, "NULL argument");
+            rc = launch_gate_up_bf16_gather(c, io->expert_offsets, c->n_local, io->max_rows, io->x, io->T, io->row_to_assign,
+                                            io->w13, io->h_mid, s);
+        }
+        if (rc != REALB_OK) return rc;
+        rc = realb_grouped_moe_ffn_down(ctx, prec, io->expert_offsets, c->n_local, io->max_rows, io->h_mid, fp4 ? io->h_s : nullptr,
+                                        fp4 ? (const void*)io->w2_q : io->w2, fp4 ? io->w2_s : nullptr, io->y_rows, stream);
+    } else if (fp4) {
         rc = realb_grouped_moe_ffn(ctx, prec, io->expert_offsets, c->n_local, io->max_rows, io->x_q, io->x_s, io->w13_q,
                                    io->w13_s, io->w2_q, io->w2_s, io->h_mid, io->h_s, io->y_rows, stream);
-    else if (gathered)
-        rc = realb_grouped_moe_ffn_down(ctx, prec, io->expert_offsets, c->n_local, io->max_rows, io->h_mid, nullptr, io->w2,
-                                        nullptr, io->y_rows, stream);
-    else
+    } else {
         rc = realb_grouped_moe_ffn(ctx, prec, io->expert_offsets, c->n_local, io->max_rows, io->x_perm, nullptr, io->w13,
                                    nullptr, io->w2, nullptr, io->h_mid, nullptr, io->y_rows, stream);
+    }
     if (rc != REALB_OK) return rc;
     rc = realb_combine(ctx, io->y_rows, io->assign_to_row, io->topk_w, io->T, io->out, stream);
     if (rc != REALB_OK) return rc;

@@ -126,7 +126,9 @@ __global__ void __launch_bounds__(256) perm_rank_kernel(const int32_t* __restric
 template <bool FP4, int CPL>   // CPL = 16-byte chunks per lane = H / 512 rounded up
 __global__ void __launch_bounds__(256) perm_gather_kernel(const u32x4_t* __restrict__ x, const int32_t* __restrict__ assign_to_row,
                                                           int T, int k, int H, u32x4_t* __restrict__ x_perm,
-                                                          uint32_t* __restrict__ x_q, uint8_t* __restrict__ x_s) {
+                                                          uint32_t* __restrict__ x_q, uint8_t* __restrict__ x_s, int token_major) {
+    // token_major: a token with a local expert is written once, at row index t (the consuming GEMM then
+    // fetches rows through row_to_assign), instead of once per row it occupies.
     const int lane = threadIdx.x & 63;
     const int chunks = H >> 3;                             // 16-B chunks per row, multiple of 16
     // A block takes a contiguous range of tokens: the rows of one 32-row group of an expert come from
@@ -161,8 +163,9 @@ __global__ void __launch_bounds__(256) perm_gather_kernel(const u32x4_t* __restr
                           ((uint32_t)__shfl_down((int)byte[u], 12) << 24);
             }
         }
-        for (int j = 0; j < k; ++j) {
-            const int r = __builtin_amdgcn_readlane(my_row, j);
+        const int n_writes = token_major ? 1 : k;
+        for (int j = 0; j < n_writes; ++j) {
+            const int r = token_major ? t : __builtin_amdgcn_readlane(my_row, j);
             if (r < 0) continue;
 #pragma unroll
             for (int u = 0; u < CPL; ++u) {
@@ -185,11 +188,11 @@ __global__ void __launch_bounds__(256) perm_gather_kernel(const u32x4_t* __restr
 
 template <bool FP4>
 static void launch_gather(int blocks, hipStream_t s, const void* x, const int32_t* a2r, int T, int k, int H, void* x_perm,
-                          uint8_t* x_q, uint8_t* x_s) {
+                          uint8_t* x_q, uint8_t* x_s, int token_major = 0) {
     const int cpl = (H / 8 + 63) / 64;
 #define REALB_GATHER(CPL)                                                                                              \
     hipLaunchKernelGGL((perm_gather_kernel<FP4, CPL>), dim3(blocks), dim3(256), 0, s, (const u32x4_t*)x, a2r, T, k, H, \
-                       (u32x4_t*)x_perm, (uint32_t*)x_q, x_s)
+                       (u32x4_t*)x_perm, (uint32_t*)x_q, x_s, token_major)
     if (cpl <= 1) REALB_GATHER(1);
     else if (cpl <= 2) REALB_GATHER(2);
     else if (cpl <= 4) REALB_GATHER(4);
@@ -230,7 +233,7 @@ int permute_indices(Ctx* c, const int32_t* topk_ids, int T, int rank, long long 
 }
 
 int permute_gather(Ctx* c, const void* x, const int32_t* assign_to_row, int T, int prec, void* x_perm, uint8_t* x_q,
-                   uint8_t* x_s, hipStream_t s) {
+                   uint8_t* x_s, hipStream_t s, int token_major) {
     REALB_REQUIRE(c != nullptr, REALB_EINVAL, "NULL argument");
     REALB_REQUIRE(prec == REALB_BF16 || prec == REALB_FP4, REALB_EINVAL, "bad precision %d", prec);
     REALB_REQUIRE(T >= 0 && T <= c->cfg.T_max, REALB_ECAP, "T=%d outside [0, T_max=%d]", T, c->cfg.T_max);
@@ -239,7 +242,7 @@ int permute_gather(Ctx* c, const void* x, const int32_t* assign_to_row, int T, i
     REALB_REQUIRE(prec == REALB_BF16 ? x_perm != nullptr : (x_q && x_s), REALB_EINVAL, "NULL row buffer");
     const int k = c->cfg.k, H = c->cfg.H;
     const int blocks = 8 * (T < 32 ? 1 : (T / 32 < 512 ? T / 32 : 512));      // a multiple of 8 (XCDs), 4 waves each
-    if (prec == REALB_FP4) launch_gather<true>(blocks, s, x, assign_to_row, T, k, H, nullptr, x_q, x_s);
+    if (prec == REALB_FP4) launch_gather<true>(blocks, s, x, assign_to_row, T, k, H, nullptr, x_q, x_s, token_major);
     else launch_gather<false>(blocks, s, x, assign_to_row, T, k, H, x_perm, nullptr, nullptr);
     REALB_HIP(hipGetLastError());
     return REALB_OK;
@@ -256,5 +259,5 @@ extern "C" int realb_permute(realb_ctx* ctx, const void* x, const int32_t* topk_
     REALB_REQUIRE(T <= 0 || (x && (prec == REALB_BF16 ? x_perm != nullptr : (x_q && x_s))), REALB_EINVAL, "NULL row buffer");
     int rc = permute_indices(c, topk_ids, T, rank, max_rows, expert_offsets, row_to_assign, assign_to_row, as_stream(stream));
     if (rc != REALB_OK) return rc;
-    return permute_gather(c, x, assign_to_row, T, prec, x_perm, x_q, x_s, as_stream(stream));
+    return permute_gather(c, x, assign_to_row, T, prec, x_perm, x_q, x_s, as_stream(stream), 0);
 }

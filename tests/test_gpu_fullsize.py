@@ -82,6 +82,14 @@ def test_full_size_layer(name):
         errs = []
         if force == R.FP4:
             xq_tok, xs_tok = omx.quantize_packed(inp["x"])                       # encode per token, gather = encode per row
+            # the layer call keeps one encoded row per token and lets the gate/up GEMM fetch rows through
+            # row_to_assign: check that form, then the permutation entry point's row-major form
+            has_local = (a2r.reshape(cfg.T, cfg.k) >= 0).any(axis=1)
+            xq_layer = buf.x_q.cpu().numpy()[:cfg.T]
+            assert np.array_equal(xq_layer[has_local], xq_tok[has_local])
+            assert np.array_equal(R.scales_to_canonical(buf.x_s, cfg.T, cfg.H)[has_local], xs_tok[has_local])
+            ctx.permute(x, buf, cfg.rank, R.FP4)
+            torch.cuda.synchronize()
             assert np.array_equal(buf.x_q.cpu().numpy()[:Rr], xq_tok[tok])
             assert np.array_equal(R.scales_to_canonical(buf.x_s, Rr, cfg.H), xs_tok[tok])
             w13s_all = R.scales_to_canonical(buf.w13_s, cfg.n_local * 2 * cfg.I, cfg.H).reshape(cfg.n_local, 2 * cfg.I, -1)
