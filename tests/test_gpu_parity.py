@@ -379,6 +379,41 @@ def test_layer_forward_policy_decides(R, case):
     assert rel_fro(obf.bits_to_f64(R.bits_from_bf16(b.out)), oo["out"]) <= tol
 
 
+@pytest.mark.parametrize("T", [1, 5, 63, 257, 1000])
+def test_fused_gather_layer_equals_step_calls_for_odd_batch_sizes(R, T):
+    """realb_layer_forward fuses the permutation's gather into the gate/up GEMM (rows fetched through
+    row_to_assign); the entry points called one by one go through the permuted copy.  Both must give the
+    same rows and outputs bit for bit, for batch sizes that leave tiles, row groups and waves partly empty."""
+    from paper_2604_19503_amd.binding import default_config
+    cfg = W.scaled(W.CONFIGS["c2"], T=T, H=512, I=256)
+    rcfg = default_config(cfg.T, cfg.E, cfg.k, cfg.D, cfg.H, cfg.I)
+    ctx = R.Context(rcfg)
+    inp = W.gen_layer(cfg, 11)
+    x, w13, w2 = (R.bf16_from_bits(inp[n]) for n in ("x", "w13", "w2"))
+    lg = torch.from_numpy(inp["logits"]).cuda(); isv = torch.from_numpy(inp["is_vision"]).cuda()
+    for prec in (R.BF16, R.FP4):
+        _say(f"fused gather T={T} prec={prec}")
+        b1 = R.LayerBuffers(rcfg, cfg.T)
+        ctx.route_stats(lg, isv, b1)
+        if prec == R.FP4:
+            ctx.quantize_experts_fp4(w13, w2, b1)
+        ctx.permute(x, b1, cfg.rank, prec)
+        ctx.grouped_moe_ffn(prec, w13, w2, b1)
+        ctx.combine(b1)
+        b2 = R.LayerBuffers(rcfg, cfg.T)
+        io = ctx.make_io(lg, isv, x, w13, w2, b2, cfg.rank, force=prec, overlap=0)
+        assert ctx.layer_forward(io) == prec
+        _sync()
+        Rr = int(b1.expert_offsets[-1])
+        assert torch.equal(b1.expert_offsets, b2.expert_offsets) and torch.equal(b1.assign_to_row, b2.assign_to_row)
+        assert torch.equal(b1.y_rows[:Rr].view(torch.int16), b2.y_rows[:Rr].view(torch.int16))
+        assert torch.equal(b1.out.view(torch.int16), b2.out.view(torch.int16))
+        o = olayer.rank_layer(inp, cfg.E, cfg.k, cfg.D, cfg.rank, 0.9, force=prec)
+        if Rr:
+            assert rel_fro(obf.bits_to_f64(R.bits_from_bf16(b2.out)), o["out"]) <= (2 * FP4_TOL if prec == R.FP4 else BF16_TOL)
+    ctx.close()
+
+
 # ---------------------------------------------------------------------------- edge cases
 def test_edge_empty_batch_and_empty_rank_and_empty_expert(R):
     from paper_2604_19503_amd.binding import default_config
