@@ -8,8 +8,9 @@ It exists beside oracle/mxfp4.py only to measure what the mapping onto MXFP4 cos
 in accuracy; no GEMM consumes it (gfx950's block-scaled matrix instructions take
 power-of-two scales).
 
-Where floating point decides an integer, the decision is taken in IEEE binary32,
-in this order (the encoder kernel takes the same steps in the same precision):
+Where floating point decides an integer, the decision is DEFINED to be taken in IEEE
+binary32 (the paper fixes no precision for it; binary32 is what a runtime encoder of
+BF16 data would naturally use), each step rounded once, in this order:
 
     amax    = max |x| over the group            (exact: a BF16 value)
     s_local = fl32(amax / 6)

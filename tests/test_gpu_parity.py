@@ -57,8 +57,6 @@ class Case:
         self.name, self.cfg, self.rank = name, spec["cfg"], spec["rank"]
         cfg = self.cfg
         inp = W.gen_layer(cfg, spec["seed"])
-        if self.rank != cfg.rank:           # weights of the rank under test
-            pass
         self.inp = inp
         from paper_2604_19503_amd.binding import default_config
         self.rcfg = default_config(cfg.T, cfg.E, cfg.k, cfg.D, cfg.H, cfg.I)
