@@ -1,144 +1,197 @@
-"""GPU parity at the full benchmark sizes (configs 2 and 3), in the launch
-configuration bench.py times (realb_layer_forward, overlap on).  Index, count and
-code tensors are compared in full and bit-exactly (the oracle's routing,
-permutation and encoder are vectorised); GEMM outputs are compared on sampled rows
-that the oracle computes one expert at a time: first and last rows of every expert
-segment (tile heads, ragged tails) plus seeded random rows."""
-import os
-import sys
+"""GPU parity at the full benchmark sizes (configs 2 and 3), in the launch configuration bench.py
+times (realb_layer_forward: fused-gather GEMMs, persistent blocks running many rounds of tiles).
 
+Index, count and code tensors are compared in full and bit-exactly.  GEMM outputs are compared
+row by row -- EVERY row of the rank, on both configs (the oracle needs well under a minute for
+the 124 516 rows of config 3 on the GPU machine's host cores) -- with three measures: the relative Frobenius norm,
+the worst per-row relative error, and an element-wise bound (tests/gpu_helpers.py).  The combine
+output is compared on every token."""
 import numpy as np
 import pytest
 import torch
 
 import workloads as W
 from oracle import bf16 as obf, ffn as offn, mxfp4 as omx, permute as operm, router as orouter
+from gpu_helpers import BF16_TOL, ROW_TOL, FP4_E2E_TOL, FP4_TOL, GATE_W_RTOL, rel_fro, row_report, same, say
 
 pytestmark = pytest.mark.gpu
 
-FP4_TOL = 2e-3
-BF16_TOL = 1e-2
-
 
 def _say(msg):
-    print(f"[gpu-fullsize] {msg}", flush=True)
-    out_dir = os.environ.get("REALB_TEST_LOG_DIR", "")     # optional: also append the progress lines to a file there
-    if out_dir and os.path.isdir(out_dir):
-        with open(os.path.join(out_dir, "parity_metrics.log"), "a") as f:
-            f.write("[fullsize] " + msg + "\n")
+    say("gpu-fullsize", msg)
 
 
-def rel_fro(a, b):
-    return float(np.linalg.norm(a - b) / np.linalg.norm(b))
+class Full:
+    def __init__(self, name):
+        import paper_2604_19503_amd as R
+        from paper_2604_19503_amd.binding import default_config
+        self.R, self.name = R, name
+        cfg = self.cfg = W.CONFIGS[name]
+        _say(f"{name}: generating inputs T={cfg.T} E={cfg.E} H={cfg.H} I={cfg.I}")
+        inp = self.inp = W.gen_layer(cfg, 0)
+        self.rcfg = default_config(cfg.T, cfg.E, cfg.k, cfg.D, cfg.H, cfg.I)
+        self.ctx = R.Context(self.rcfg)
+        self.buf = R.LayerBuffers(self.rcfg, cfg.T)
+        self.lg = torch.from_numpy(inp["logits"]).cuda()
+        self.isv = torch.from_numpy(inp["is_vision"]).cuda()
+        self.x, self.w13, self.w2 = (R.bf16_from_bits(inp[n]) for n in ("x", "w13", "w2"))
+        _say(f"{name}: oracle routing and permutation")
+        self.ids, self.w = orouter.topk_route(inp["logits"], cfg.k)
+        self.counts = orouter.route_counts(self.ids, inp["is_vision"], cfg.E, cfg.D)
+        self.off, self.r2a, self.a2r = operm.permute_indices(self.ids, cfg.rank, cfg.n_local)
+        self.rows = int(self.off[-1])
+        self.tok = self.r2a.astype(np.int64) // cfg.k
+        self.experts = list(range(cfg.n_local))                      # every row of the rank, one expert at a time
+        self._fp4 = None
+
+    def fp4_operands(self):
+        """The oracle's encodings of the weights (all experts) and of the tokens."""
+        if self._fp4 is None:
+            _say(f"{self.name}: oracle encodes weights and tokens")
+            w13q, w13s = omx.quantize(self.inp["w13"])
+            w2q, w2s = omx.quantize(self.inp["w2"])
+            xq_tok, xs_tok = omx.quantize_packed(self.inp["x"])
+            self._fp4 = (w13q, w13s, w2q, w2s, xq_tok, xs_tok)
+        return self._fp4
+
+    def check_indices(self):
+        b, cfg = self.buf, self.cfg
+        cnt, vis, load, rvis = self.counts
+        assert same(b.topk_ids.cpu().numpy(), self.ids)
+        assert np.allclose(b.topk_w.cpu().numpy().astype(np.float64), self.w, rtol=GATE_W_RTOL, atol=1e-9)
+        assert same(b.expert_cnt.cpu().numpy(), cnt) and same(b.expert_vis.cpu().numpy(), vis)
+        assert same(b.rank_load.cpu().numpy(), load) and same(b.rank_vis.cpu().numpy(), rvis)
+        assert same(b.expert_offsets.cpu().numpy(), self.off)
+        assert same(b.row_to_assign.cpu().numpy()[:self.rows], self.r2a)
+        assert same(b.assign_to_row.cpu().numpy(), self.a2r)
+
+    def check_combine(self, tol):
+        """out on EVERY token against the oracle's combine of the GPU's own rows (stage-isolated)."""
+        b, cfg, R = self.buf, self.cfg, self.R
+        y_bits = R.bits_from_bf16(b.y_rows[:max(self.rows, 1)])
+        want = offn.combine(y_bits, self.a2r, self.w, cfg.T, cfg.k)
+        got = obf.bits_to_f64(R.bits_from_bf16(b.out))
+        fro = rel_fro(got, want)
+        worst_row, n_bad, excess = row_report(got, want)
+        _say(f"{self.name}: combine, all {cfg.T} tokens: rel fro {fro:.3e}, worst token {worst_row:.3e}, "
+             f"elements outside the bound {n_bad} (worst {excess:.2f} of it)")
+        assert fro <= tol and worst_row <= ROW_TOL and n_bad == 0
+        none_local = (self.a2r.reshape(cfg.T, cfg.k) < 0).all(axis=1)
+        assert not got[none_local].any()
+        return got
 
 
-def _sample_rows(off, rng, per_expert=6):
-    rows = []
-    for e in range(len(off) - 1):
-        lo, hi = int(off[e]), int(off[e + 1])
+@pytest.fixture(scope="module", params=["c2", "c3"])
+def full(request):
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU")
+    f = Full(request.param)
+    yield f
+    f.ctx.close()
+
+
+def test_full_size_fp4(full):
+    f, R, cfg, b = full, full.R, full.cfg, full.buf
+    _say(f"{f.name}: layer_forward FP4, rows={f.rows}, experts compared row by row: {f.experts}")
+    b.y_rows.fill_(float("nan"))
+    io = f.ctx.make_io(f.lg, f.isv, f.x, f.w13, f.w2, b, cfg.rank, force=R.FP4, overlap=True)
+    assert f.ctx.layer_forward(io) == R.FP4
+    torch.cuda.synchronize()
+    f.check_indices()
+    w13q, w13s, w2q, w2s, xq_tok, xs_tok = f.fp4_operands()
+    # weights: codes and scales of every expert
+    assert same(b.w13_q.cpu().numpy(), omx.pack(w13q))
+    assert same(R.scales_to_canonical(b.w13_s, cfg.n_local * 2 * cfg.I, cfg.H).reshape(w13s.shape), w13s)
+    assert same(b.w2_q.cpu().numpy(), omx.pack(w2q))
+    assert same(R.scales_to_canonical(b.w2_s, cfg.n_local * cfg.H, cfg.I).reshape(w2s.shape), w2s)
+    # activations: the layer call keeps one encoded row per token that has a local expert
+    has_local = (f.a2r.reshape(cfg.T, cfg.k) >= 0).any(axis=1)
+    assert same(b.x_q.cpu().numpy()[:cfg.T][has_local], xq_tok[has_local])
+    assert same(R.scales_to_canonical(b.x_s, cfg.T, cfg.H)[has_local], xs_tok[has_local])
+    y_gpu = R.bits_from_bf16(b.y_rows[:f.rows])
+    assert torch.isnan(b.y_rows[f.rows:f.rows + 4096].float()).all()            # nothing written past R
+    hs_all = R.scales_to_canonical(b.h_s, f.rows, cfg.I)
+    hq_all = b.h_mid.view(torch.uint8).reshape(-1)[: b.max_rows * (cfg.I // 2)].reshape(b.max_rows, cfg.I // 2)[:f.rows].cpu().numpy()
+    num_st = num_e2e = den = 0.0
+    worst_row = worst_excess = 0.0
+    n_bad = n_rows = 0
+    flips_max = 0.0
+    for e in f.experts:
+        lo, hi = int(f.off[e]), int(f.off[e + 1])
         if hi <= lo:
             continue
-        pick = {lo, hi - 1, lo + (hi - lo) // 2, min(lo + 255, hi - 1), min(lo + 256, hi - 1)}
-        pick |= set(int(v) for v in rng.integers(lo, hi, per_expert))
-        rows.append((e, np.array(sorted(pick))))
-    return rows
+        t = f.tok[lo:hi]
+        seg = [0, hi - lo]
+        hq, hs, y = offn.ffn_fp4(omx.unpack(xq_tok[t]), xs_tok[t], w13q[e:e + 1], w13s[e:e + 1], w2q[e:e + 1], w2s[e:e + 1], seg)
+        hq_g, hs_g = omx.unpack(hq_all[lo:hi]), hs_all[lo:hi]
+        scale_diff = hs_g != hs
+        code_diff = (hq_g != hq) & ~np.repeat(scale_diff, 32, axis=1)
+        flips = float(code_diff.mean() + scale_diff.mean())
+        flips_max = max(flips_max, flips)
+        if code_diff.any():
+            assert np.abs((hq_g[code_diff] & 7).astype(int) - (hq[code_diff] & 7).astype(int)).max() <= 1
+        # stage-isolated: the oracle's down GEMM on the GPU's own intermediate codes
+        y_st = offn.down_fp4(hq_g, hs_g, w2q[e:e + 1], w2s[e:e + 1], seg)
+        yg = obf.bits_to_f64(y_gpu[lo:hi])
+        assert np.isfinite(yg).all()
+        num_st += float(np.sum((yg - y_st) ** 2)); num_e2e += float(np.sum((yg - y) ** 2)); den += float(np.sum(y_st ** 2))
+        wr, nb, ex = row_report(yg, y_st)
+        worst_row, worst_excess, n_bad, n_rows = max(worst_row, wr), max(worst_excess, ex), n_bad + nb, n_rows + hi - lo
+        _say(f"{f.name}: expert {e}: {hi - lo} rows, staged rel fro {rel_fro(yg, y_st):.3e}, end to end {rel_fro(yg, y):.3e}, "
+             f"worst row {wr:.3e}, h flips {flips:.2e}")
+    staged, e2e = (num_st / den) ** 0.5, (num_e2e / den) ** 0.5
+    _say(f"{f.name}: fp4, {n_rows} of {f.rows} rows compared: staged rel fro {staged:.3e}, end to end {e2e:.3e}, worst row (staged) "
+         f"{worst_row:.3e}, elements outside the bound {n_bad} (worst {worst_excess:.2f} of it), h flips max {flips_max:.2e}")
+    assert staged <= FP4_TOL and e2e <= FP4_E2E_TOL
+    assert worst_row <= ROW_TOL and n_bad == 0
+    assert flips_max <= 1e-3
+    f.check_combine(FP4_TOL)
+    # the permutation entry point's own row-major form of the encoded activations
+    f.ctx.permute(f.x, b, cfg.rank, R.FP4)
+    torch.cuda.synchronize()
+    assert same(b.x_q.cpu().numpy()[:f.rows], xq_tok[f.tok])
+    assert same(R.scales_to_canonical(b.x_s, f.rows, cfg.H), xs_tok[f.tok])
 
 
-@pytest.mark.parametrize("name", ["c2", "c3"])
-def test_full_size_layer(name):
-    import paper_2604_19503_amd as R
-    from paper_2604_19503_amd.binding import default_config
-    cfg = W.CONFIGS[name]
-    _say(f"{name}: generating inputs T={cfg.T} E={cfg.E} H={cfg.H} I={cfg.I}")
-    inp = W.gen_layer(cfg, 0)
-    rcfg = default_config(cfg.T, cfg.E, cfg.k, cfg.D, cfg.H, cfg.I)
-    ctx = R.Context(rcfg)
-    buf = R.LayerBuffers(rcfg, cfg.T)
-    lg = torch.from_numpy(inp["logits"]).cuda()
-    isv = torch.from_numpy(inp["is_vision"]).cuda()
-    x, w13, w2 = (R.bf16_from_bits(inp[n]) for n in ("x", "w13", "w2"))
-    # oracle side that does not depend on the precision
-    ids, w = orouter.topk_route(inp["logits"], cfg.k)
-    cnt, vis, load, rvis = orouter.route_counts(ids, inp["is_vision"], cfg.E, cfg.D)
-    off, r2a, a2r = operm.permute_indices(ids, cfg.rank, cfg.n_local)
-    Rr = int(off[-1])
-    rng = np.random.default_rng(5)
-    samples = _sample_rows(off, rng)
-    x_f = None
-    for force in (R.FP4, R.BF16):
-        _say(f"{name}: layer_forward force={force} rows={Rr}")
-        io = ctx.make_io(lg, isv, x, w13, w2, buf, cfg.rank, force=force, overlap=True)
-        assert ctx.layer_forward(io) == force
-        torch.cuda.synchronize()
-        assert np.array_equal(buf.topk_ids.cpu().numpy(), ids)
-        assert np.allclose(buf.topk_w.cpu().numpy().astype(np.float64), w, rtol=1e-6, atol=1e-9)
-        assert np.array_equal(buf.expert_cnt.cpu().numpy(), cnt) and np.array_equal(buf.expert_vis.cpu().numpy(), vis)
-        assert np.array_equal(buf.rank_load.cpu().numpy(), load) and np.array_equal(buf.rank_vis.cpu().numpy(), rvis)
-        assert np.array_equal(buf.expert_offsets.cpu().numpy(), off)
-        assert np.array_equal(buf.row_to_assign.cpu().numpy()[:Rr], r2a)
-        assert np.array_equal(buf.assign_to_row.cpu().numpy(), a2r)
-        tok = r2a.astype(np.int64) // cfg.k
-        y_gpu = R.bits_from_bf16(buf.y_rows[:Rr])
-        errs = []
-        if force == R.FP4:
-            xq_tok, xs_tok = omx.quantize_packed(inp["x"])                       # encode per token, gather = encode per row
-            # the layer call keeps one encoded row per token and lets the gate/up GEMM fetch rows through
-            # row_to_assign: check that form, then the permutation entry point's row-major form
-            has_local = (a2r.reshape(cfg.T, cfg.k) >= 0).any(axis=1)
-            xq_layer = buf.x_q.cpu().numpy()[:cfg.T]
-            assert np.array_equal(xq_layer[has_local], xq_tok[has_local])
-            assert np.array_equal(R.scales_to_canonical(buf.x_s, cfg.T, cfg.H)[has_local], xs_tok[has_local])
-            ctx.permute(x, buf, cfg.rank, R.FP4)
-            torch.cuda.synchronize()
-            assert np.array_equal(buf.x_q.cpu().numpy()[:Rr], xq_tok[tok])
-            assert np.array_equal(R.scales_to_canonical(buf.x_s, Rr, cfg.H), xs_tok[tok])
-            w13s_all = R.scales_to_canonical(buf.w13_s, cfg.n_local * 2 * cfg.I, cfg.H).reshape(cfg.n_local, 2 * cfg.I, -1)
-            w2s_all = R.scales_to_canonical(buf.w2_s, cfg.n_local * cfg.H, cfg.I).reshape(cfg.n_local, cfg.H, -1)
-            hs_all = R.scales_to_canonical(buf.h_s, Rr, cfg.I)
-            hq_gpu = buf.h_mid.view(torch.uint8).reshape(-1)[: buf.max_rows * (cfg.I // 2)].reshape(buf.max_rows, cfg.I // 2)
-            for e, rows in samples:
-                w13q, w13s = omx.quantize(inp["w13"][e:e + 1])
-                w2q, w2s = omx.quantize(inp["w2"][e:e + 1])
-                assert np.array_equal(buf.w13_q[e].cpu().numpy(), omx.pack(w13q[0]))
-                assert np.array_equal(w13s_all[e], w13s[0])
-                assert np.array_equal(buf.w2_q[e].cpu().numpy(), omx.pack(w2q[0]))
-                assert np.array_equal(w2s_all[e], w2s[0])
-                xq = omx.unpack(xq_tok[tok[rows]])
-                hq, hs, y = offn.ffn_fp4(xq, xs_tok[tok[rows]], w13q, w13s, w2q, w2s, [0, len(rows)])
-                # stage-isolated: the oracle's down GEMM on the GPU's own intermediate codes
-                hq_g = omx.unpack(hq_gpu[torch.from_numpy(rows).cuda()].cpu().numpy())
-                hs_g = hs_all[rows]
-                flips = (hq_g != hq).mean()
-                assert flips <= 2e-3, (e, flips)
-                y_st = offn.down_fp4(hq_g, hs_g, w2q, w2s, [0, len(rows)])
-                yg = obf.bits_to_f64(y_gpu[rows])
-                errs.append((rel_fro(yg, y_st), rel_fro(yg, y)))
-            staged = max(a for a, _ in errs)
-            full = max(b for _, b in errs)
-            _say(f"{name}: fp4 sampled rows: staged rel fro max {staged:.3e}, end-to-end max {full:.3e}")
-            assert staged <= FP4_TOL and full <= 3 * FP4_TOL
-        else:
-            # the layer call fetches the BF16 rows through row_to_assign inside the gate/up GEMM and need not
-            # materialise x_perm; the permutation entry point itself is checked here
-            ctx.permute(x, buf, cfg.rank, R.BF16)
-            torch.cuda.synchronize()
-            assert np.array_equal(R.bits_from_bf16(buf.x_perm[:Rr]), inp["x"][tok])
-            for e, rows in samples:
-                _, y = offn.ffn_bf16(inp["x"][tok[rows]], inp["w13"][e:e + 1], inp["w2"][e:e + 1], [0, len(rows)])
-                errs.append(rel_fro(obf.bits_to_f64(y_gpu[rows]), y))
-            _say(f"{name}: bf16 sampled rows: rel fro max {max(errs):.3e}")
-            assert max(errs) <= BF16_TOL
-        # combine on sampled tokens, from the GPU's own rows (stage-isolated)
-        toks = np.unique(tok[np.concatenate([r for _, r in samples])])[:256]
-        out_gpu = obf.bits_to_f64(R.bits_from_bf16(buf.out[torch.from_numpy(toks).cuda()]))
-        want = np.zeros_like(out_gpu)
-        for i, t in enumerate(toks):
-            for j in range(cfg.k):
-                r = a2r[t * cfg.k + j]
-                if r >= 0:
-                    want[i] += w[t, j] * obf.bits_to_f64(y_gpu[r])
-        assert rel_fro(out_gpu, want) <= (FP4_TOL if force == R.FP4 else BF16_TOL)
-        none_local = np.nonzero((a2r.reshape(cfg.T, cfg.k) < 0).all(axis=1))[0][:64]
-        if none_local.size:
-            assert not buf.out[torch.from_numpy(none_local).cuda()].float().abs().sum().item()
-    ctx.close()
+def test_full_size_bf16(full):
+    f, R, cfg, b = full, full.R, full.cfg, full.buf
+    _say(f"{f.name}: layer_forward BF16, rows={f.rows}, experts compared row by row: {f.experts}")
+    b.y_rows.fill_(float("nan"))
+    io = f.ctx.make_io(f.lg, f.isv, f.x, f.w13, f.w2, b, cfg.rank, force=R.BF16, overlap=True)
+    assert f.ctx.layer_forward(io) == R.BF16
+    torch.cuda.synchronize()
+    f.check_indices()
+    y_gpu = R.bits_from_bf16(b.y_rows[:f.rows])
+    assert torch.isnan(b.y_rows[f.rows:f.rows + 4096].float()).all()
+    h_gpu = R.bits_from_bf16(b.h_mid[:f.rows])
+    num = num_st = den = 0.0
+    worst_row = worst_excess = 0.0
+    n_bad = n_rows = 0
+    for e in f.experts:
+        lo, hi = int(f.off[e]), int(f.off[e + 1])
+        if hi <= lo:
+            continue
+        seg = [0, hi - lo]
+        h_bits, y = offn.ffn_bf16(f.inp["x"][f.tok[lo:hi]], f.inp["w13"][e:e + 1], f.inp["w2"][e:e + 1], seg)
+        differ = float((h_gpu[lo:hi] != h_bits).mean())
+        assert differ <= 5e-3                                            # nearest-even boundary flips only
+        # stage-isolated: the oracle's down GEMM on the GPU's own h
+        y_st = offn.down(obf.bits_to_f64(h_gpu[lo:hi]), obf.bits_to_f64(f.inp["w2"][e:e + 1]), seg)
+        yg = obf.bits_to_f64(y_gpu[lo:hi])
+        assert np.isfinite(yg).all()
+        num += float(np.sum((yg - y) ** 2)); num_st += float(np.sum((yg - y_st) ** 2)); den += float(np.sum(y ** 2))
+        wr, nb, ex = row_report(yg, y_st)
+        wr2, nb2, ex2 = row_report(yg, y)                                # and against the oracle's own h
+        worst_row, worst_excess, n_bad, n_rows = max(worst_row, wr, wr2), max(worst_excess, ex, ex2), n_bad + nb + nb2, n_rows + hi - lo
+        _say(f"{f.name}: expert {e}: {hi - lo} rows, rel fro {rel_fro(yg, y):.3e} (staged {rel_fro(yg, y_st):.3e}), worst row {max(wr, wr2):.3e}, "
+             f"h patterns differing {differ:.2e}")
+    e2e, staged = (num / den) ** 0.5, (num_st / den) ** 0.5
+    _say(f"{f.name}: bf16, {n_rows} of {f.rows} rows compared: rel fro {e2e:.3e} (staged {staged:.3e}), worst row {worst_row:.3e}, "
+         f"elements outside the bound {n_bad} (worst {worst_excess:.2f} of it)")
+    assert e2e <= BF16_TOL and staged <= BF16_TOL and worst_row <= ROW_TOL and n_bad == 0
+    f.check_combine(BF16_TOL)
+    # the layer call fetches the rows through row_to_assign inside the gate/up GEMM and need not materialise
+    # x_perm; the permutation entry point itself is checked here
+    f.ctx.permute(f.x, b, cfg.rank, R.BF16)
+    torch.cuda.synchronize()
+    assert same(R.bits_from_bf16(b.x_perm[:f.rows]), f.inp["x"][f.tok])
