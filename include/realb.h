@@ -97,6 +97,20 @@ int realb_route_stats(realb_ctx* ctx, const float* logits, const uint8_t* is_vis
                       int32_t* topk_ids, float* topk_w, int32_t* expert_cnt, int32_t* expert_vis,
                       int32_t* rank_load, int32_t* rank_vis, void* stream);
 
+/* realb_route_stats for callers that cannot allocate device memory and hold no context: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results and
+ * kernels as realb_route_stats, with the shape passed directly; the per-block partial histograms, which
+ * realb_route_stats keeps in the context's workspace, live in a 2 MiB array inside the library's device
+ * image (one copy per GPU, held until the process ends).  Calls no hipMalloc / hipFree and no allocating
+ * library routine; the array's address is looked up on the first call on a device (or by realb_create).
+ * Limits: E <= 512 (REALB_ECAP beyond), 1 <= k <= min(E, 16), E a multiple of D, T*k < 2^31.
+ * All calls on one GPU share the array: calls that overlap on one GPU (different streams or threads)
+ * race and are not supported; calls ordered on one stream, or otherwise serialised, are fine.  Nothing
+ * needs clearing between calls. */
+int realb_route_stats_static(const float* logits, const uint8_t* is_vision, int T, int E, int k, int D,
+                             int32_t* topk_ids, float* topk_w, int32_t* expert_cnt, int32_t* expert_vis,
+                             int32_t* rank_load, int32_t* rank_vis, void* stream);
+
 /* Stage 2, modality-aware LB scheduling: LB gate (T > Gamma), AIMD update of M,
  * hotspot set {d : IB_d > C}, FP4 iff hotspot and R_vd > M (Sec. "Real-time
  * Modality-aware LB Scheduling", "LB Gate").  force = REALB_BF16 / REALB_FP4

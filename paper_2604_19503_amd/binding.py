@@ -16,7 +16,7 @@ EXPORTS = [
     "realb_route_stats", "realb_select_precision", "realb_select_precision_host", "realb_quantize_experts_fp4",
     "realb_quantize_rows_fp4", "realb_permute", "realb_grouped_moe_ffn", "realb_grouped_moe_ffn_gate_up",
     "realb_grouped_moe_ffn_down", "realb_set_gemm_tile", "realb_combine", "realb_layer_forward", "realb_rank_forward",
-    "realb_quantize_rows_nvfp4", "realb_amax_bf16",
+    "realb_quantize_rows_nvfp4", "realb_amax_bf16", "realb_route_stats_static",
 ]
 
 
@@ -69,6 +69,7 @@ def load_library() -> C.CDLL:
     lib.realb_destroy.argtypes = [C.c_void_p]
     vp = C.c_void_p
     lib.realb_route_stats.argtypes = [vp, vp, vp, C.c_int, vp, vp, vp, vp, vp, vp, vp]
+    lib.realb_route_stats_static.argtypes = [vp, vp, C.c_int, C.c_int, C.c_int, C.c_int, vp, vp, vp, vp, vp, vp, vp]
     lib.realb_select_precision.argtypes = [vp, vp, vp, C.c_int, C.c_int, vp, vp, vp, vp]
     lib.realb_select_precision_host.argtypes = [C.POINTER(Config), vp, vp, C.c_int, C.c_int, vp, vp, vp]
     lib.realb_quantize_experts_fp4.argtypes = [vp, vp, vp, C.c_int, vp, vp, vp, vp, vp]
@@ -171,6 +172,15 @@ def quantize_rows_nvfp4(x: torch.Tensor, global_scale: float, stream=None):
     s = torch.empty((rows, K // 16), dtype=torch.uint8, device=x.device)
     _check(load_library().realb_quantize_rows_nvfp4(_p(x), rows, K, C.c_float(global_scale), _p(q), _p(s), _stream(stream)))
     return q, s
+
+
+def route_stats_static(logits, is_vision, E: int, k: int, D: int, b, T=None, stream=None):
+    """realb_route_stats_static: the routing call that allocates nothing and needs no context; writes into
+    the caller's buffers b (topk_ids, topk_w, expert_cnt, expert_vis, rank_load, rank_vis)."""
+    T = logits.shape[0] if T is None else T
+    _check(load_library().realb_route_stats_static(_p(logits), _p(is_vision), T, E, k, D, _p(b.topk_ids), _p(b.topk_w),
+                                                   _p(b.expert_cnt), _p(b.expert_vis), _p(b.rank_load), _p(b.rank_vis),
+                                                   _stream(stream)))
 
 
 class LayerBuffers:

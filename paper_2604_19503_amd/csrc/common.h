@@ -43,6 +43,9 @@ int launch_gate_up_fp4_gather(Ctx* c, const int32_t* expert_offsets, int n_local
 int permute_gather(Ctx* c, const void* x, const int32_t* assign_to_row, int T, int prec, void* x_perm, uint8_t* x_q,
                    uint8_t* x_s, hipStream_t s, int token_major);
 int hip_fail(hipError_t e, const char* what);
+// Address (on the current device) of the file-scope scratch array of realb_route_stats_static and the device's CU
+// count; looked up once per device and cached.  Either output may be NULL.
+int static_scratch_lookup(int32_t** ptr, int* num_cus);
 
 #define REALB_HIP(call)                                                        \
     do {                                                                       \

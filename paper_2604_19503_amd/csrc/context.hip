@@ -119,6 +119,12 @@ int realb_create(const realb_config* cfg, realb_ctx** out) {
         realb_destroy(reinterpret_cast<realb_ctx*>(c));
         return hip_fail(e, "realb_create");
     }
+    // set-up for the allocation-free routing call on this device (address of its static scratch array)
+    rc = static_scratch_lookup(nullptr, nullptr);
+    if (rc != REALB_OK) {
+        realb_destroy(reinterpret_cast<realb_ctx*>(c));
+        return rc;
+    }
     *out = reinterpret_cast<realb_ctx*>(c);
     return REALB_OK;
 }

@@ -4,6 +4,7 @@
 // assignment counts, split by modality.
 #include "common.h"
 #include <math.h>
+#include <mutex>
 
 namespace realb {
 
@@ -218,9 +219,87 @@ __global__ void __launch_bounds__(1024) hist_reduce_kernel(const int32_t* __rest
         for (int e = 0; e < n_local; ++e) { load += tot[d * n_local + e]; vis += tot[E + d * n_local + e]; }
         rank_load[d] = load;
         rank_vis[d] = vis;
-        stats_host[d] = load;                         // pinned host copy for the policy: saves two copy launches
-        stats_host[D + d] = vis;
+        if (stats_host) {                             // pinned host copy for the policy: saves two copy launches
+            stats_host[d] = load;
+            stats_host[D + d] = vis;
+        }
     }
+}
+
+// Launches the top-k + histogram kernel and the reduce.  hist_part must hold max_blocks * 2E counters;
+// stats_host (pinned host memory) may be NULL.
+static int launch_route_stats(int num_cus, int max_blocks, int32_t* hist_part, int32_t* stats_host, const float* logits,
+                              const uint8_t* is_vision, int T, int E, int k, int D, int32_t* topk_ids, float* topk_w,
+                              int32_t* expert_cnt, int32_t* expert_vis, int32_t* rank_load, int32_t* rank_vis, hipStream_t s) {
+    int blocks = 0;
+    if (T > 0) {
+        const size_t lds = 2 * (size_t)E * sizeof(int32_t);
+        if (E <= 128 && E % 16 == 0) {                          // four tokens per wave
+            blocks = min(min(ceil_div(T, 64), 2 * num_cus), max_blocks);      // 16 waves x 4 tokens in flight per block, two blocks per CU
+#define REALB_TOPK_ROWS(EPL)                                                                                      \
+    hipLaunchKernelGGL(topk_hist_rows_kernel<EPL>, dim3(blocks), dim3(1024), lds, s, logits, is_vision, T, E, k, \
+                       topk_ids, topk_w, hist_part)
+            switch (E / 16) {
+                case 1: REALB_TOPK_ROWS(1); break;
+                case 2: REALB_TOPK_ROWS(2); break;
+                case 3: REALB_TOPK_ROWS(3); break;
+                case 4: REALB_TOPK_ROWS(4); break;
+                case 5: REALB_TOPK_ROWS(5); break;
+                case 6: REALB_TOPK_ROWS(6); break;
+                case 7: REALB_TOPK_ROWS(7); break;
+                default: REALB_TOPK_ROWS(8); break;
+            }
+#undef REALB_TOPK_ROWS
+        } else {
+            blocks = min(min(ceil_div(T, 16), 2 * num_cus), max_blocks);      // 16 waves (tokens in flight) per block, two blocks per CU
+            const int epl = ceil_div(E, 64);
+#define REALB_TOPK(EPL)                                                                                      \
+    hipLaunchKernelGGL(topk_hist_kernel<EPL>, dim3(blocks), dim3(1024), lds, s, logits, is_vision, T, E, k, \
+                       topk_ids, topk_w, hist_part)
+            if (epl == 1) REALB_TOPK(1);
+            else if (epl == 2) REALB_TOPK(2);
+            else if (epl <= 4) REALB_TOPK(4);
+            else REALB_TOPK(8);
+#undef REALB_TOPK
+        }
+    }
+    hipLaunchKernelGGL(hist_reduce_kernel, dim3(1), dim3(1024), 2 * (size_t)E * sizeof(int32_t), s, hist_part, blocks, E, D,
+                       expert_cnt, expert_vis, rank_load, rank_vis, stats_host);
+    REALB_HIP(hipGetLastError());
+    return REALB_OK;
+}
+
+// ---- the allocation-free variant's scratch: the per-block partial histograms, in a file-scope device array.
+// Every GPU the library runs on holds its own copy at its own address until the process ends; the address is
+// looked up once per device (with that device current) and kept, and host code only ever uses that pointer.
+constexpr int kStaticBlocksMax = 512;                     // two blocks per CU on 256 CUs
+constexpr int kStaticEMax = 512;
+constexpr size_t kStaticCounters = (size_t)kStaticBlocksMax * 2 * kStaticEMax;      // 2 MiB of int32
+static __device__ __align__(256) int32_t scratch[kStaticCounters];
+
+constexpr int kMaxDevices = 64;
+struct StaticSlot { int32_t* ptr; int num_cus; };
+static StaticSlot g_static[kMaxDevices];                  // zero-initialised; filled once per device under g_static_mu
+static std::mutex g_static_mu;
+
+// The current device's scratch pointer and CU count (looked up on the first call on that device).
+int static_scratch_lookup(int32_t** ptr, int* num_cus) {
+    int dev = 0;
+    REALB_HIP(hipGetDevice(&dev));
+    REALB_REQUIRE(dev >= 0 && dev < kMaxDevices, REALB_ECAP, "device index %d exceeds %d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static[dev].ptr) {
+        int32_t* p = nullptr;
+        int cus = 0;
+        REALB_HIP(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+        REALB_HIP(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+        REALB_REQUIRE(p != nullptr && cus > 0, REALB_EHIP, "no address for the static scratch array on device %d", dev);
+        g_static[dev].num_cus = cus;
+        g_static[dev].ptr = p;
+    }
+    if (ptr) *ptr = g_static[dev].ptr;
+    if (num_cus) *num_cus = g_static[dev].num_cus;
+    return REALB_OK;
 }
 
 }  // namespace realb
@@ -234,42 +313,26 @@ extern "C" int realb_route_stats(realb_ctx* ctx, const float* logits, const uint
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     REALB_REQUIRE(T >= 0 && T <= c->cfg.T_max, REALB_ECAP, "T=%d outside [0, T_max=%d]", T, c->cfg.T_max);
     REALB_REQUIRE(T == 0 || (logits && is_vision && topk_ids && topk_w), REALB_EINVAL, "NULL argument");
-    hipStream_t s = as_stream(stream);
-    const int E = c->cfg.E, k = c->cfg.k, D = c->cfg.D;
-    int blocks = 0;
-    if (T > 0) {
-        const size_t lds = 2 * (size_t)E * sizeof(int32_t);
-        if (E <= 128 && E % 16 == 0) {                          // four tokens per wave
-            blocks = min(ceil_div(T, 64), 2 * c->num_cus);      // 16 waves x 4 tokens in flight per block, two blocks per CU
-#define REALB_TOPK_ROWS(EPL)                                                                                      \
-    hipLaunchKernelGGL(topk_hist_rows_kernel<EPL>, dim3(blocks), dim3(1024), lds, s, logits, is_vision, T, E, k, \
-                       topk_ids, topk_w, c->hist_part)
-            switch (E / 16) {
-                case 1: REALB_TOPK_ROWS(1); break;
-                case 2: REALB_TOPK_ROWS(2); break;
-                case 3: REALB_TOPK_ROWS(3); break;
-                case 4: REALB_TOPK_ROWS(4); break;
-                case 5: REALB_TOPK_ROWS(5); break;
-                case 6: REALB_TOPK_ROWS(6); break;
-                case 7: REALB_TOPK_ROWS(7); break;
-                default: REALB_TOPK_ROWS(8); break;
-            }
-#undef REALB_TOPK_ROWS
-        } else {
-            blocks = min(ceil_div(T, 16), 2 * c->num_cus);      // 16 waves (tokens in flight) per block, two blocks per CU
-            const int epl = ceil_div(E, 64);
-#define REALB_TOPK(EPL)                                                                                      \
-    hipLaunchKernelGGL(topk_hist_kernel<EPL>, dim3(blocks), dim3(1024), lds, s, logits, is_vision, T, E, k, \
-                       topk_ids, topk_w, c->hist_part)
-            if (epl == 1) REALB_TOPK(1);
-            else if (epl == 2) REALB_TOPK(2);
-            else if (epl <= 4) REALB_TOPK(4);
-            else REALB_TOPK(8);
-#undef REALB_TOPK
-        }
-    }
-    hipLaunchKernelGGL(hist_reduce_kernel, dim3(1), dim3(1024), 2 * (size_t)E * sizeof(int32_t), s, c->hist_part, blocks, E, D,
-                       expert_cnt, expert_vis, rank_load, rank_vis, c->stats_host);
-    REALB_HIP(hipGetLastError());
-    return REALB_OK;
+    return launch_route_stats(c->num_cus, 2 * c->num_cus, c->hist_part, c->stats_host, logits, is_vision, T, c->cfg.E, c->cfg.k,
+                              c->cfg.D, topk_ids, topk_w, expert_cnt, expert_vis, rank_load, rank_vis, as_stream(stream));
+}
+
+extern "C" int realb_route_stats_static(const float* logits, const uint8_t* is_vision, int T, int E, int k, int D,
+                                        int32_t* topk_ids, float* topk_w, int32_t* expert_cnt, int32_t* expert_vis,
+                                        int32_t* rank_load, int32_t* rank_vis, void* stream) {
+    REALB_REQUIRE(expert_cnt && expert_vis && rank_load && rank_vis, REALB_EINVAL, "NULL argument");
+    REALB_REQUIRE(E > 0 && k > 0 && D > 0 && E % D == 0, REALB_ESHAPE, "E=%d must be a positive multiple of D=%d", E, D);
+    REALB_REQUIRE(E <= kStaticEMax, REALB_ECAP, "E=%d exceeds the static scratch array's maximum of %d experts", E, kStaticEMax);
+    REALB_REQUIRE(k <= E && k <= 16, REALB_ESHAPE, "k=%d must be <= min(E,16)", k);
+    REALB_REQUIRE(T >= 0 && (long long)T * k < (1ll << 31), REALB_ECAP, "T=%d: T*k must stay below 2^31", T);
+    REALB_REQUIRE(T == 0 || (logits && is_vision && topk_ids && topk_w), REALB_EINVAL, "NULL argument");
+    int32_t* part = nullptr;
+    int num_cus = 0;
+    const int rc = static_scratch_lookup(&part, &num_cus);
+    if (rc != REALB_OK) return rc;
+    // every block overwrites its whole slice of the array and the reduce reads only the slices of this launch,
+    // so nothing has to be cleared between calls
+    const int max_blocks = (int)(kStaticCounters / (2 * (size_t)E)) < kStaticBlocksMax ? (int)(kStaticCounters / (2 * (size_t)E)) : kStaticBlocksMax;
+    return launch_route_stats(num_cus, max_blocks, part, nullptr, logits, is_vision, T, E, k, D, topk_ids, topk_w, expert_cnt,
+                              expert_vis, rank_load, rank_vis, as_stream(stream));
 }
