@@ -33,7 +33,8 @@
  *   - Return value: REALB_OK or a negative error code; realb_last_error() gives
  *     the message of the calling thread's last failure.  Nothing aborts or throws.
  *     Non-finite inputs are outside the contract.
- *   - Shapes: H and I multiples of 128, H <= 8192; E a multiple of D; 1 <= k <= min(E, 16);
+ *   - Shapes: H and I multiples of 128 (one K-step of the GEMMs is 128 bytes of a BF16 row or 256 FP4
+ *     values, and scale tensors are tiled by 128-element K-steps), H <= 8192; E a multiple of D; 1 <= k <= min(E, 16);
  *     E <= 512; n_local = E/D <= 64.  Expert e lives on rank e / n_local.
  */
 #ifndef REALB_H
@@ -77,6 +78,19 @@ void realb_default_config(realb_config* cfg, int T_max, int E, int k, int D, int
 int realb_create(const realb_config* cfg, realb_ctx** out);
 int realb_destroy(realb_ctx* ctx);
 const char* realb_last_error(void);
+
+/* Device memory, in bytes, that realb_create allocates for this configuration (the permutation's per-chunk
+ * counters and the routing kernel's per-block partial histograms); besides it a context holds 8*D bytes of
+ * pinned host memory, one stream and three events.  Host-only, no GPU needed; 0 for an unsupported shape
+ * (realb_last_error says why). */
+size_t realb_workspace_bytes(const realb_config* cfg);
+
+/* Where the E8M0 scale of (row, 32-element block kb) of a matrix [rows, K] lives in a K-step-tiled scale
+ * tensor (the formula of the conventions above, as the library itself evaluates it); (size_t)-1 for
+ * arguments out of range.  realb_scale_index_map writes the offsets of every (row, kb), row-major
+ * [rows, K/32], to host memory: canonical[row][kb] = tiled[idx[row][kb]].  Host-only. */
+size_t realb_scale_offset(long long row, int kb, int K);
+int realb_scale_index_map(long long rows, int K, int64_t* idx_host);
 
 /* The AIMD threshold M carried across layers (host scalar). */
 double realb_get_M(const realb_ctx* ctx);

@@ -17,6 +17,7 @@ EXPORTS = [
     "realb_quantize_rows_fp4", "realb_permute", "realb_grouped_moe_ffn", "realb_grouped_moe_ffn_gate_up",
     "realb_grouped_moe_ffn_down", "realb_set_gemm_tile", "realb_combine", "realb_layer_forward", "realb_rank_forward",
     "realb_quantize_rows_nvfp4", "realb_amax_bf16", "realb_route_stats_static",
+    "realb_workspace_bytes", "realb_scale_offset", "realb_scale_index_map",
 ]
 
 
@@ -65,6 +66,11 @@ def load_library() -> C.CDLL:
     lib.realb_set_M.argtypes = [C.c_void_p, C.c_double]
     lib.realb_default_config.restype = None
     lib.realb_default_config.argtypes = [C.POINTER(Config)] + [C.c_int] * 6
+    lib.realb_workspace_bytes.restype = C.c_size_t
+    lib.realb_workspace_bytes.argtypes = [C.POINTER(Config)]
+    lib.realb_scale_offset.restype = C.c_size_t
+    lib.realb_scale_offset.argtypes = [C.c_longlong, C.c_int, C.c_int]
+    lib.realb_scale_index_map.argtypes = [C.c_longlong, C.c_int, C.c_void_p]
     lib.realb_create.argtypes = [C.POINTER(Config), C.POINTER(C.c_void_p)]
     lib.realb_destroy.argtypes = [C.c_void_p]
     vp = C.c_void_p
@@ -111,16 +117,22 @@ def bf16_from_bits(bits: np.ndarray, device="cuda") -> torch.Tensor:
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device).view(torch.bfloat16)
 
 
+def scale_index_map(rows: int, K: int) -> np.ndarray:
+    """realb_scale_index_map: int64 [rows, K/32] byte offsets into a K-step-tiled scale tensor."""
+    idx = np.empty((rows, K // 32), dtype=np.int64)
+    _check(load_library().realb_scale_index_map(rows, K, idx.ctypes.data))
+    return idx
+
+
+def workspace_bytes(cfg: Config) -> int:
+    return int(load_library().realb_workspace_bytes(C.byref(cfg)))
+
+
 def scales_to_canonical(s, rows: int, K: int) -> np.ndarray:
     """Pure index permutation (no arithmetic): a K-step-tiled scale tensor, as the library reads
-    and writes it, rearranged to the plain [rows, K/32] order.  Byte (row, kb) of the tiled tensor
-    sits at (((row//32)*KD + kb//4)*32 + row%32)*4 + kb%4 with KD = K/128."""
+    and writes it, rearranged to the plain [rows, K/32] order through the library's own index map."""
     flat = (s.detach().cpu().numpy() if isinstance(s, torch.Tensor) else np.asarray(s)).reshape(-1)
-    KD = K // 128
-    row = np.arange(rows, dtype=np.int64)[:, None]
-    kb = np.arange(K // 32, dtype=np.int64)[None, :]
-    idx = (((row >> 5) * KD + (kb >> 2)) * 32 + (row & 31)) * 4 + (kb & 3)
-    return flat[idx]
+    return flat[scale_index_map(rows, K)]
 
 
 def bits_from_bf16(t: torch.Tensor) -> np.ndarray:

@@ -10,6 +10,7 @@ namespace realb {
 
 constexpr int kWave = 64;
 constexpr int kPermChunk = 256;    // assignments ranked by one wave in permute
+constexpr int kRouteBlocksMax = 512;   // most blocks the routing kernel is launched with (two per CU on 256 CUs)
 
 struct Ctx {
     realb_config cfg;
@@ -20,7 +21,7 @@ struct Ctx {
     // device workspace
     int32_t* wave_cnt;     // [n_chunks_max, n_local]  per-chunk local-expert counts, then exclusive bases
     int n_chunks_max;
-    int32_t* hist_part;    // [num_cus, 2*E]  per-block partial histograms of route_stats
+    int32_t* hist_part;    // [kRouteBlocksMax, 2*E]  per-block partial histograms of route_stats
     // pinned host staging for the policy's inputs
     int32_t* stats_host;   // [2*D]
     hipStream_t side;      // side stream for the weight encoder

@@ -1,5 +1,6 @@
 // Context, error reporting and the host-side precision policy.
 #include "common.h"
+#include "mxfp4_device.h"
 #include <string.h>
 #include <new>
 
@@ -33,6 +34,11 @@ static int check_shape(const realb_config* c) {
     REALB_REQUIRE((long long)c->T_max * c->k < (1ll << 31), REALB_ESHAPE, "T_max*k overflows int32");
     return REALB_OK;
 }
+
+// The two device buffers of a context's workspace.
+static int n_chunks_max(const realb_config* c) { return ceil_div((long long)c->T_max * c->k, kPermChunk) + 1; }
+static size_t wave_cnt_bytes(const realb_config* c) { return (size_t)n_chunks_max(c) * (c->E / c->D) * sizeof(int32_t); }
+static size_t hist_part_bytes(const realb_config* c) { return (size_t)kRouteBlocksMax * 2 * c->E * sizeof(int32_t); }
 
 // Precision policy (paper Sec. "Real-time Modality-aware LB Scheduling" and "LB
 // Gate").  Ratios are never formed: IB_d > C is load_d*D > C*(T*k), IB_global >
@@ -106,10 +112,9 @@ int realb_create(const realb_config* cfg, realb_ctx** out) {
     c->wave_cnt = nullptr; c->hist_part = nullptr; c->stats_host = nullptr; c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr; c->ev_stats = nullptr;
     hipError_t e = hipGetDevice(&c->device);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&c->num_cus, hipDeviceAttributeMultiprocessorCount, c->device);
-    long long A_max = (long long)cfg->T_max * cfg->k;
-    c->n_chunks_max = ceil_div(A_max, kPermChunk) + 1;
-    if (e == hipSuccess) e = hipMalloc((void**)&c->wave_cnt, (size_t)c->n_chunks_max * c->n_local * sizeof(int32_t));
-    if (e == hipSuccess) e = hipMalloc((void**)&c->hist_part, (size_t)c->num_cus * 2 * 2 * cfg->E * sizeof(int32_t));   // two blocks per CU x [2][E]
+    c->n_chunks_max = n_chunks_max(cfg);
+    if (e == hipSuccess) e = hipMalloc((void**)&c->wave_cnt, wave_cnt_bytes(cfg));
+    if (e == hipSuccess) e = hipMalloc((void**)&c->hist_part, hist_part_bytes(cfg));
     if (e == hipSuccess) e = hipHostMalloc((void**)&c->stats_host, 2 * cfg->D * sizeof(int32_t), hipHostMallocDefault);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
@@ -140,6 +145,25 @@ int realb_destroy(realb_ctx* ctx) {
     if (c->ev_stats) (void)hipEventDestroy(c->ev_stats);
     if (c->side) (void)hipStreamDestroy(c->side);
     delete c;
+    return REALB_OK;
+}
+
+size_t realb_workspace_bytes(const realb_config* cfg) {
+    if (check_shape(cfg) != REALB_OK) return 0;
+    return wave_cnt_bytes(cfg) + hist_part_bytes(cfg);
+}
+
+size_t realb_scale_offset(long long row, int kb, int K) {
+    if (row < 0 || kb < 0 || K <= 0 || K % 128 != 0 || kb >= K / 32) return (size_t)-1;
+    return scale_byte_offset(row, kb, K >> 7);
+}
+
+int realb_scale_index_map(long long rows, int K, int64_t* idx_host) {
+    REALB_REQUIRE(rows >= 0 && K > 0 && K % 128 == 0, REALB_ESHAPE, "rows=%lld K=%d: K must be a positive multiple of 128", rows, K);
+    REALB_REQUIRE(rows == 0 || idx_host != nullptr, REALB_EINVAL, "NULL argument");
+    const int nb = K / 32, KD = K >> 7;
+    for (long long r = 0; r < rows; ++r)
+        for (int kb = 0; kb < nb; ++kb) idx_host[r * nb + kb] = (int64_t)scale_byte_offset(r, kb, KD);
     return REALB_OK;
 }
 

@@ -25,8 +25,18 @@
 // store.  expert_offsets is read on the device, so no host round trip.
 #include "common.h"
 #include "mxfp4_device.h"
+#include <atomic>
 
 namespace realb {
+
+// Devices (bit = device index) on which a kernel instantiation has had its dynamic-LDS limit raised.
+static bool first_use_on_device(std::atomic<unsigned long long>& seen, int device) {
+    const unsigned long long bit = 1ull << (device & 63);
+    return (seen.load(std::memory_order_acquire) & bit) == 0;
+}
+static void mark_used_on_device(std::atomic<unsigned long long>& seen, int device) {
+    seen.fetch_or(1ull << (device & 63), std::memory_order_release);
+}
 
 typedef __attribute__((ext_vector_type(8))) int v8i_t;
 typedef __attribute__((ext_vector_type(16))) float v16f_t;
@@ -743,14 +753,15 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
 }
 
 template <bool FP4, bool GATEUP, bool GATHER = false>
-static int launch_gemm256(GemmParams p, long long max_rows, int num_cus, hipStream_t s) {
+static int launch_gemm256(GemmParams p, long long max_rows, const Ctx* c, hipStream_t s) {
+    const int num_cus = c->num_cus;
     p.n_tiles_n = p.n_out / (GATEUP ? 128 : 256);
     const size_t lds = t256::LDS_BYTES;
-    static bool attr_done = false;
-    if (!attr_done) {
+    static std::atomic<unsigned long long> attr_seen{0};            // per instantiation, one bit per device
+    if (first_use_on_device(attr_seen, c->device)) {                // (setting it twice from two threads is harmless)
         REALB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_gemm256_kernel<FP4, GATEUP, GATHER>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
-        attr_done = true;
+        mark_used_on_device(attr_seen, c->device);
     }
     const long long m_tiles_max = (max_rows + BM - 1) / BM + p.n_local;
     const long long total_max = m_tiles_max * p.n_tiles_n;
@@ -765,16 +776,17 @@ static int launch_gemm256(GemmParams p, long long max_rows, int num_cus, hipStre
 // where the output width is a multiple of its tile); the register-staged kernel with 64-byte K-steps
 // as 2 = 256x128, 4 waves, two blocks per CU, or 8 = 256x256, 8 waves of 128x64, one block per CU.
 template <bool FP4, bool GATEUP, int WN, int WGN, int MINB>
-static int launch_gemm_geo(GemmParams p, long long max_rows, int num_cus, hipStream_t s) {
+static int launch_gemm_geo(GemmParams p, long long max_rows, const Ctx* c, hipStream_t s) {
     using G = Geo<WN, WGN>;
+    const int num_cus = c->num_cus;
     p.n_tiles_n = GATEUP ? p.n_out / G::GC : p.n_out / G::BNW;
     const size_t lds = 2 * (size_t)G::STAGE;
     const size_t lds_cap = MINB == 2 ? 80 * 1024 : 160 * 1024;
-    static bool attr_done = false;                                   // per instantiation
-    if (!attr_done) {
+    static std::atomic<unsigned long long> attr_seen{0};            // per instantiation, one bit per device
+    if (first_use_on_device(attr_seen, c->device)) {
         REALB_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_gemm_kernel<FP4, GATEUP, WN, WGN, MINB>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_cap));
-        attr_done = true;
+        mark_used_on_device(attr_seen, c->device);
     }
     const long long m_tiles_max = (max_rows + BM - 1) / BM + p.n_local;
     const long long total_max = m_tiles_max * p.n_tiles_n;
@@ -788,22 +800,24 @@ static int launch_gemm_geo(GemmParams p, long long max_rows, int num_cus, hipStr
     return REALB_OK;
 }
 
-static int g_tile = 0;    // 0 = automatic; 2, 8 or 16 forces a kernel (set through realb_set_gemm_tile)
+static std::atomic<int> g_tile{0};    // 0 = automatic; 2, 8 or 16 forces a kernel (set through realb_set_gemm_tile)
 
 template <bool FP4, bool GATEUP>
-static int launch_gemm(const GemmParams& p, long long max_rows, int num_cus, hipStream_t s) {
+static int launch_gemm(const GemmParams& p, long long max_rows, const Ctx* c, hipStream_t s) {
     const int unit256 = GATEUP ? 128 : 256;             // output columns per block of the 256-wide tile
     const bool can256 = p.n_out % unit256 == 0;
-    const int sel = !can256 ? 2 : (g_tile == 0 ? 16 : g_tile);
-    if (sel == 16) return launch_gemm256<FP4, GATEUP>(p, max_rows, num_cus, s);
-    if (sel == 8) return launch_gemm_geo<FP4, GATEUP, 2, 4, 1>(p, max_rows, num_cus, s);
-    return launch_gemm_geo<FP4, GATEUP, 2, 2, 2>(p, max_rows, num_cus, s);
+    const int forced = g_tile.load(std::memory_order_relaxed);
+    const int sel = !can256 ? 2 : (forced == 0 ? 16 : forced);
+    if (sel == 16) return launch_gemm256<FP4, GATEUP>(p, max_rows, c, s);
+    if (sel == 8) return launch_gemm_geo<FP4, GATEUP, 2, 4, 1>(p, max_rows, c, s);
+    return launch_gemm_geo<FP4, GATEUP, 2, 2, 2>(p, max_rows, c, s);
 }
 
 // Whether the gathering gate/up GEMM below applies (kernel selection, 32-bit row offsets).
 bool gate_up_gather_supported(const Ctx* c, int T, bool fp4) {
     const long long bytes = (long long)T * c->cfg.H * (fp4 ? 1 : 4) / 2;
-    return (g_tile == 0 || g_tile == 16) && c->cfg.I % 128 == 0 && T > 0 && bytes < (1ll << 32);
+    const int forced = g_tile.load(std::memory_order_relaxed);
+    return (forced == 0 || forced == 16) && c->cfg.I % 128 == 0 && T > 0 && bytes < (1ll << 32);
 }
 
 // BF16 gate/up GEMM that gathers its activation rows from the token matrix x [T,H] through row_to_assign
@@ -815,7 +829,7 @@ int launch_gate_up_bf16_gather(Ctx* c, const int32_t* expert_offsets, int n_loca
     if (!gate_up_gather_supported(c, T, false)) return REALB_ESHAPE;
     GemmParams g{(const uint8_t*)x, nullptr, (const uint8_t*)w13, nullptr, (uint8_t*)h_mid, nullptr, expert_offsets, n_local,
                  H, 2 * I, I, 0, row_to_assign, c->cfg.k};
-    return launch_gemm256<false, true, true>(g, max_rows, c->num_cus, s);
+    return launch_gemm256<false, true, true>(g, max_rows, c, s);
 }
 
 // The same for the FP4 path: x_q / x_s hold one encoded row per TOKEN (row index = token index).
@@ -825,7 +839,7 @@ int launch_gate_up_fp4_gather(Ctx* c, const int32_t* expert_offsets, int n_local
     const int H = c->cfg.H, I = c->cfg.I;
     if (!gate_up_gather_supported(c, T, true)) return REALB_ESHAPE;
     GemmParams g{x_q, x_s, w13_q, w13_s, h_q, h_s, expert_offsets, n_local, H, 2 * I, I, 0, row_to_assign, c->cfg.k};
-    return launch_gemm256<true, true, true>(g, max_rows, c->num_cus, s);
+    return launch_gemm256<true, true, true>(g, max_rows, c, s);
 }
 
 }  // namespace realb
@@ -834,7 +848,7 @@ using namespace realb;
 
 extern "C" int realb_set_gemm_tile(int wn) {
     REALB_REQUIRE(wn == 0 || wn == 2 || wn == 8 || wn == 16, REALB_EINVAL, "tile selector must be 0, 2, 8 or 16");
-    g_tile = wn;
+    g_tile.store(wn, std::memory_order_relaxed);
     return REALB_OK;
 }
 
@@ -857,11 +871,11 @@ static int ffn_stages(realb_ctx* ctx, int prec, int stages, const int32_t* exper
     GemmParams g2{(const uint8_t*)h_mid, h_s, (const uint8_t*)w2, w2_s, (uint8_t*)y_rows, nullptr, expert_offsets, n_local, I, H, H, 0, nullptr, 1};
     int rc = REALB_OK;
     if (prec == REALB_FP4) {
-        if (s1) rc = launch_gemm<true, true>(g1, max_rows, c->num_cus, s);
-        if (rc == REALB_OK && s2) rc = launch_gemm<true, false>(g2, max_rows, c->num_cus, s);
+        if (s1) rc = launch_gemm<true, true>(g1, max_rows, c, s);
+        if (rc == REALB_OK && s2) rc = launch_gemm<true, false>(g2, max_rows, c, s);
     } else {
-        if (s1) rc = launch_gemm<false, true>(g1, max_rows, c->num_cus, s);
-        if (rc == REALB_OK && s2) rc = launch_gemm<false, false>(g2, max_rows, c->num_cus, s);
+        if (s1) rc = launch_gemm<false, true>(g1, max_rows, c, s);
+        if (rc == REALB_OK && s2) rc = launch_gemm<false, false>(g2, max_rows, c, s);
     }
     return rc;
 }

@@ -272,7 +272,7 @@ static int launch_route_stats(int num_cus, int max_blocks, int32_t* hist_part, i
 // ---- the allocation-free variant's scratch: the per-block partial histograms, in a file-scope device array.
 // Every GPU the library runs on holds its own copy at its own address until the process ends; the address is
 // looked up once per device (with that device current) and kept, and host code only ever uses that pointer.
-constexpr int kStaticBlocksMax = 512;                     // two blocks per CU on 256 CUs
+constexpr int kStaticBlocksMax = kRouteBlocksMax;
 constexpr int kStaticEMax = 512;
 constexpr size_t kStaticCounters = (size_t)kStaticBlocksMax * 2 * kStaticEMax;      // 2 MiB of int32
 static __device__ __align__(256) int32_t scratch[kStaticCounters];
@@ -313,7 +313,7 @@ extern "C" int realb_route_stats(realb_ctx* ctx, const float* logits, const uint
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     REALB_REQUIRE(T >= 0 && T <= c->cfg.T_max, REALB_ECAP, "T=%d outside [0, T_max=%d]", T, c->cfg.T_max);
     REALB_REQUIRE(T == 0 || (logits && is_vision && topk_ids && topk_w), REALB_EINVAL, "NULL argument");
-    return launch_route_stats(c->num_cus, 2 * c->num_cus, c->hist_part, c->stats_host, logits, is_vision, T, c->cfg.E, c->cfg.k,
+    return launch_route_stats(c->num_cus, kRouteBlocksMax, c->hist_part, c->stats_host, logits, is_vision, T, c->cfg.E, c->cfg.k,
                               c->cfg.D, topk_ids, topk_w, expert_cnt, expert_vis, rank_load, rank_vis, as_stream(stream));
 }
 

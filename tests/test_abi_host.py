@@ -117,3 +117,50 @@ def test_bad_force_value_is_an_error():
     cfg = binding.default_config(64, 8, 2, 1, 128, 128)
     with pytest.raises(R.RealbError):
         R.select_precision_host(cfg, [128], [0], 64, 0.9, force=7)
+
+
+def test_workspace_bytes_is_host_only_and_matches_its_definition():
+    lib = R.load_library()
+    cfg = binding.default_config(16384, 64, 6, 8, 2048, 1408)
+    n_chunks = -(-16384 * 6 // 256) + 1
+    assert binding.workspace_bytes(cfg) == n_chunks * 8 * 4 + 512 * 2 * 64 * 4
+    small = binding.default_config(0, 8, 2, 1, 256, 128)
+    assert binding.workspace_bytes(small) == 1 * 8 * 4 + 512 * 2 * 8 * 4
+    bad = binding.default_config(128, 64, 6, 7, 2048, 1408)            # E not a multiple of D
+    assert binding.workspace_bytes(bad) == 0 and lib.realb_last_error()
+    assert lib.realb_workspace_bytes(None) == 0
+
+
+def test_scale_offset_and_index_map_describe_the_tiled_layout():
+    lib = R.load_library()
+    # the layout as the header words it: the 4 scales of one row at one 128-element K-step form a dword,
+    # the dwords of 32 consecutive rows are contiguous, K-steps follow, then the next group of 32 rows
+    K, rows = 384, 70
+    KD = K // 128
+    idx = binding.scale_index_map(rows, K)
+    assert idx.shape == (rows, K // 32)
+    want = np.empty_like(idx)
+    pos = 0
+    for group in range(-(-rows // 32)):
+        for step in range(KD):
+            for r in range(32):
+                for b in range(4):
+                    row = group * 32 + r
+                    if row < rows:
+                        want[row, step * 4 + b] = pos
+                    pos += 1
+    assert np.array_equal(idx, want)
+    assert len(np.unique(idx)) == idx.size and idx.max() < -(-rows // 32) * 32 * (K // 32)
+    for row, kb in ((0, 0), (31, 11), (32, 0), (69, 7)):
+        assert lib.realb_scale_offset(row, kb, K) == idx[row, kb]
+    bad = C.c_size_t(-1).value
+    assert lib.realb_scale_offset(0, 12, K) == bad and lib.realb_scale_offset(-1, 0, K) == bad and lib.realb_scale_offset(0, 0, 100) == bad
+    assert lib.realb_scale_index_map(4, 100, None) == -2
+    assert lib.realb_scale_index_map(0, 128, None) == 0
+
+
+def test_gemm_tile_selector_accepts_only_its_values():
+    lib = R.load_library()
+    for v in (2, 8, 16, 0):
+        assert lib.realb_set_gemm_tile(v) == 0
+    assert lib.realb_set_gemm_tile(3) == -1

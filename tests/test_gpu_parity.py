@@ -482,4 +482,20 @@ def test_capacity_and_argument_errors(R, case):
     small.max_rows = 1
     with pytest.raises(R.RealbError):
         case.ctx.permute(case.x, small, 0, R.BF16)
+    # the layer calls refuse bad arguments before anything reaches the side stream, in every encoder placement,
+    # and the context stays usable
+    for overlap in (3, 1, 0):
+        io = case.ctx.make_io(case.logits, case.is_vision, case.x, case.w13, case.w2, b, case.rank, force=R.FP4, overlap=overlap)
+        io.max_rows = 1
+        with pytest.raises(R.RealbError):
+            case.ctx.layer_forward(io)
+        with pytest.raises(R.RealbError):
+            case.ctx.rank_forward(io, R.FP4)
+        io.max_rows = b.max_rows
+        io.force = 7
+        with pytest.raises(R.RealbError):
+            case.ctx.layer_forward(io)
+    _sync()
+    io = case.ctx.make_io(case.logits, case.is_vision, case.x, case.w13, case.w2, b, case.rank, force=R.FP4, overlap=3)
+    assert case.ctx.layer_forward(io) == R.FP4
     _sync()
