@@ -49,13 +49,100 @@ if ROOT not in sys.path:
 
 PEAK_TFLOPS = {"fp4": 10100.0, "bf16": 2500.0}     # MI355X dense MFMA peaks
 PEAK_HBM_GBS = 8000.0
+PREROLL_MS = 150.0                                  # untimed steps before the timed region, beyond --warmup
+ENCODE_MODES = ("prefetch", "speculative", "side", "main")
+MODE_ID = {"speculative": 3, "side": 1, "main": 0}
+
+
+class LayerRun:
+    """One workload's inputs, context and buffers on the device, and its step functions."""
+
+    def __init__(self, workload, args, torch, W, R, default_config):
+        self.torch, self.R, self.args = torch, R, args
+        cfg = self.cfg = W.CONFIGS[workload]
+        self.inp = W.gen_layer(cfg, 0)
+        self.rcfg = default_config(cfg.T, cfg.E, cfg.k, cfg.D, cfg.H, cfg.I)
+        self.ctx = R.Context(self.rcfg)
+        self.buf = R.LayerBuffers(self.rcfg, cfg.T)
+        self.lg = torch.from_numpy(self.inp["logits"]).cuda()
+        self.isv = torch.from_numpy(self.inp["is_vision"]).cuda()
+        self.x, self.w13, self.w2 = (R.bf16_from_bits(self.inp[n]) for n in ("x", "w13", "w2"))
+        self.reserve = args.reserve_cus
+        self._pair = None
+
+    def close(self):
+        self.ctx.prefetch_join()
+        self.torch.cuda.synchronize()
+        self.ctx.close()
+
+    def stepper(self, fp4: bool, mode: str):
+        """A function that runs one whole rank-layer step.  mode "prefetch": the steady state of a layer pipeline --
+        two layers with distinct weights alternate, each call consumes the FP4 weights the previous call encoded beside
+        its GEMMs and encodes the other layer's weights beside its own (every step still encodes one full weight set)."""
+        R, ctx = self.R, self.ctx
+        force = R.FP4 if fp4 else R.BF16
+        if not (fp4 and mode == "prefetch"):
+            io = ctx.make_io(self.lg, self.isv, self.x, self.w13, self.w2, self.buf, self.cfg.rank, force=force, overlap=MODE_ID[mode])
+            return lambda: ctx.layer_forward(io)
+        if self._pair is None:
+            import workloads as W
+            wB = tuple(R.bf16_from_bits(a) for a in W.gen_weights(self.cfg, 1))
+            self._pair = ([(self.w13, self.w2), wB], [R.WeightBuffers(self.rcfg), R.WeightBuffers(self.rcfg)])
+        ws, wbufs = self._pair
+        ios = []
+        for i in (0, 1):
+            io = ctx.make_io(self.lg, self.isv, self.x, ws[i][0], ws[i][1], self.buf, self.cfg.rank, force=force, overlap=4)
+            ctx.use_weight_buffers(io, wbufs[i])
+            ctx.set_prefetch(io, ws[1 - i][0], ws[1 - i][1], wbufs[1 - i], self.reserve)
+            ios.append(io)
+        ctx.quantize_experts_fp4(ws[0][0], ws[0][1], wbufs[0])           # the first layer has nobody to prefetch for it
+        state = {"i": 0}
+
+        def step():
+            ctx.layer_forward(ios[state["i"]])
+            state["i"] ^= 1
+        return step
+
+    def stage_pass(self, step, steps):
+        """Mean GPU ms per stage of the layer call over `steps` steps (library-recorded events)."""
+        ctx = self.ctx
+        ctx.stage_timing(True)
+        acc = {}
+        for _ in range(steps):
+            step()
+            for n, v in ctx.stage_ms().items():
+                acc[n] = acc.get(n, 0.0) + v
+        ctx.stage_timing(False)
+        return {n: v / steps for n, v in acc.items()}
+
+    def brief(self, fp4: bool, mode: str, warm: int = 30, steps: int = 30):
+        """A short timing of the layer in one precision: ms per step, FFN rate, GEMM stage times."""
+        torch = self.torch
+        step = self.stepper(fp4, mode)
+        for _ in range(warm):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            step()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        st = self.stage_pass(step, 10)
+        self.ctx.prefetch_join()
+        rows = int(self.buf.expert_offsets[-1].item())
+        flops = 6.0 * rows * self.cfg.H * self.cfg.I
+        peak = PEAK_TFLOPS["fp4" if fp4 else "bf16"]
+        gemm = flops / ((st["gate_up"] + st["down"]) * 1e-3) / 1e12
+        return {"layer_ms": ms, "rows_on_rank": rows, "step_tflops": flops / (ms * 1e-3) / 1e12, "encode_mode": mode if fp4 else None,
+                "gate_up_ms": st["gate_up"], "down_ms": st["down"], "grouped_gemm_tflops": gemm, "grouped_gemm_frac_of_peak": gemm / peak,
+                "gate_up_frac_of_peak": 4.0 * rows * self.cfg.H * self.cfg.I / (st["gate_up"] * 1e-3) / 1e12 / peak}
 
 
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=300, help="untimed steps first; the clocks need about 100 ms of load to settle")
+    ap.add_argument("--warmup", type=int, default=20, help="untimed steps first (a fixed 150 ms pre-roll follows in any case: the clocks need about 100 ms of load to settle)")
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "gate-sweep", "policy-ablation", "format-gap"],
                     help="c2 (default) is the headline line; c4 = 8-rank imbalance simulation, c5 = 48-layer overlap stress, "
                          "gate-sweep = FP4 vs BF16 layer time over the batch size (locates the LB gate), "
@@ -65,10 +152,14 @@ def parse():
     ap.add_argument("--iterations", type=int, default=100, help="trace length of the policy ablation")
     ap.add_argument("--precision", default="fp4", choices=["fp4", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--encode-mode", default="speculative", choices=["speculative", "side", "main"],
-                    help="where the FP4 weight encoding runs: side stream before routing (default: measured fastest), main stream "
-                         "after the decision, or side stream after the decision (under the permutation); the step is timed in "
-                         "all three and reported under extra")
+    ap.add_argument("--encode-mode", default="speculative", choices=list(ENCODE_MODES),
+                    help="where the FP4 weight encoding runs: speculative (default) = side stream before routing, beside the routing and "
+                         "index kernels; prefetch = layer pipeline, each step encodes the next layer's weights on the side stream beside "
+                         "its own GEMMs; main = caller's "
+                         "stream after the decision; side = side stream after the decision (under the permutation).  The step is timed "
+                         "in all of them, in rotated order, and reported under extra")
+    ap.add_argument("--reserve-cus", type=int, default=0, help="compute units the GEMMs leave to the encoder in prefetch mode")
+    ap.add_argument("--no-compare", action="store_true", help="skip the brief BF16 pass and the c3 pair folded into the default line")
     ap.add_argument("--gemm-tile", type=int, default=0, choices=[0, 2, 8, 16], help="grouped-GEMM block tile selector (0 = automatic)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 512 MiB device copy (untimed) so that a counter run can scale FETCH_SIZE / WRITE_SIZE")
@@ -234,6 +325,24 @@ def run_c5(args):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / (layers * max(1, min(args.steps, 5)))
 
+    # cross-layer prefetch: layer l consumes what layer l-1's call encoded beside its GEMMs and encodes layer l+1's
+    # weights beside its own; the GEMMs' persistent grids leave `reserve` compute units to the encoder
+    pair = [R.WeightBuffers(rcfg), R.WeightBuffers(rcfg)]
+    ms_prefetch = {}
+    for reserve in ((args.reserve_cus,) if args.steps < 3 else (0, 8, 16, 24, 32, 48)):
+        pios = []
+        for l in range(layers):
+            io = ctx.make_io(lg, isv, x, weights[l][0], weights[l][1], buf, cfg.rank, force=R.FP4, overlap=4)
+            ctx.use_weight_buffers(io, pair[l & 1])
+            nw = weights[(l + 1) % layers]
+            ctx.set_prefetch(io, nw[0], nw[1], pair[(l + 1) & 1], reserve)
+            pios.append(io)
+        ios[("prefetch", reserve)] = pios
+        ctx.quantize_experts_fp4(weights[0][0], weights[0][1], pair[0])
+        ms_prefetch[reserve] = timed(("prefetch", reserve))
+        ctx.prefetch_join()
+        torch.cuda.synchronize()
+    best_reserve = min(ms_prefetch, key=ms_prefetch.get)
     ms_overlap = timed(1)
     ms_seq = timed(0)
     ms_spec = timed(3)
@@ -253,13 +362,16 @@ def run_c5(args):
     qms, _ = event_ms(lambda: ctx.quantize_experts_fp4(weights[1][0], weights[1][1], buf), 20, torch)
     n_w = cfg.n_local * 3 * cfg.H * cfg.I
     rows = int(buf.expert_offsets[-1].item())
-    result = {"metric": "per-layer ms over 48 layers of distinct weights, FP4 path, weight encoding issued speculatively on the side stream",
-              "value": ms_spec, "unit": "ms", "n_gpus": 1, "steps": layers, "warmup": layers, "ms_per_step": ms_spec,
+    ms_pf = ms_prefetch[best_reserve]
+    result = {"metric": "per-layer ms over 48 layers of distinct weights, FP4 path, each layer's weights encoded beside the previous layer's GEMMs",
+              "value": ms_pf, "unit": "ms", "n_gpus": 1, "steps": layers, "warmup": layers, "ms_per_step": ms_pf,
               "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
               "dtype": "fp4 (MXFP4 E2M1 + E8M0/32, fp32 accumulate)", "data": "synthetic",
               "config": {"workload": "c5: Qwen3-VL-shaped rank, 128 experts top-8, 16 local, H=2048 I=768, T=65536 tokens, "
                                      "85% vision, 48 distinct BF16 weight sets"},
-              "extra": {"rows_on_rank": rows, "layer_ms_overlap": ms_overlap, "layer_ms_sequential": ms_seq,
+              "extra": {"rows_on_rank": rows, "layer_ms_prefetch_by_reserved_cus": {str(k_): round(v, 5) for k_, v in ms_prefetch.items()},
+                        "reserved_cus": best_reserve, "exposed_encoding_ms_prefetch": ms_pf - ms_noquant,
+                        "layer_ms_overlap": ms_overlap, "layer_ms_sequential": ms_seq,
                         "layer_ms_weights_pre_encoded": ms_noquant, "exposed_encoding_ms_overlap": ms_overlap - ms_noquant,
                         "exposed_encoding_ms_sequential": ms_seq - ms_noquant, "layer_ms_speculative": ms_spec,
                         "exposed_encoding_ms_speculative": ms_spec - ms_noquant, "encoder_alone_ms": qms,
@@ -521,48 +633,58 @@ def main():
         return run_format_gap(args)
     cfg = W.CONFIGS[args.workload]
     fp4 = args.precision == "fp4"
-    force = R.FP4 if fp4 else R.BF16
-    inp = W.gen_layer(cfg, 0)
-    rcfg = default_config(cfg.T, cfg.E, cfg.k, cfg.D, cfg.H, cfg.I)
-    ctx = R.Context(rcfg)
-    buf = R.LayerBuffers(rcfg, cfg.T)
-    lg = torch.from_numpy(inp["logits"]).cuda()
-    isv = torch.from_numpy(inp["is_vision"]).cuda()
-    x, w13, w2 = (R.bf16_from_bits(inp[n]) for n in ("x", "w13", "w2"))
-    mode_id = {"speculative": 3, "side": 1, "main": 0}
-    io = ctx.make_io(lg, isv, x, w13, w2, buf, cfg.rank, force=force, overlap=mode_id[args.encode_mode])
+    lr = LayerRun(args.workload, args, torch, W, R, default_config)
+    mode = args.encode_mode if fp4 else "main"
 
-    def step():
-        ctx.layer_forward(io)
-
+    # ---- warm-up: the driver's W steps, then a fixed, declared pre-roll (the clocks need about 100 ms of load to settle)
+    step = lr.stepper(fp4, mode)
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    ms_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    by_mode = {args.encode_mode: ms_step}
-    if fp4:                                      # the other two placements of the weight encoding, for comparison
-        for name, mid in mode_id.items():
-            if name == args.encode_mode:
-                continue
-            io.overlap = mid
+    preroll_steps = 0
+    while (time.perf_counter() - t0) * 1e3 < PREROLL_MS:
+        for _ in range(20):
             step()
+        torch.cuda.synchronize()
+        preroll_steps += 20
+    preroll_ms = (time.perf_counter() - t0) * 1e3
+
+    # ---- timed region: exactly K steps of the headline placement.  The other placements of the weight encoding are
+    #      timed beside it in rotated order (K steps each as well, in `rounds` chunks), so that no placement always
+    #      runs first or last.
+    modes = [mode] + [m for m in ENCODE_MODES if m != mode] if fp4 else [mode]
+    steppers = {m: (step if m == mode else lr.stepper(fp4, m)) for m in modes}
+    rounds = max(1, min(4, args.steps))
+    chunk = [args.steps // rounds + (1 if r < args.steps % rounds else 0) for r in range(rounds)]
+    total = {m: 0.0 for m in modes}
+    for r in range(rounds):
+        order = modes[r % len(modes):] + modes[:r % len(modes)]
+        for m in order:
+            f = steppers[m]
+            if m != mode or r > 0:
+                f(); f()                                  # (switching placements: two untimed steps)
             torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for _ in range(args.steps):
-                step()
+            t1 = time.perf_counter()
+            for _ in range(chunk[r]):
+                f()
             torch.cuda.synchronize()
-            by_mode[name] = (time.perf_counter() - t0) * 1e3 / args.steps
-        io.overlap = mode_id[args.encode_mode]
-    rows = int(buf.expert_offsets[-1].item())
+            total[m] += time.perf_counter() - t1
+    lr.ctx.prefetch_join()
+    by_mode = {m: total[m] * 1e3 / args.steps for m in modes}
+    ms_step = by_mode[mode]
+    rows = int(lr.buf.expert_offsets[-1].item())
     H, I, T, k = cfg.H, cfg.I, cfg.T, cfg.k
     ffn_flops = 6.0 * rows * H * I
 
-    # ---- per-kernel breakdown on the same stream (separate pass, not part of the timed steps)
+    # ---- the stages of the very call the step makes, timed by events the library records at its stage boundaries
+    #      (a separate pass of K steps: the events cost a few microseconds per call)
+    layer_stages = lr.stage_pass(step, args.steps)
+
+    # ---- the entry points one by one on the same stream (separate pass)
     n_w = cfg.n_local * 3 * H * I
+    ctx, buf, x, w13, w2, lg, isv = lr.ctx, lr.buf, lr.x, lr.w13, lr.w2, lr.lg, lr.isv
+    force = R.FP4 if fp4 else R.BF16
     tok_local = int((buf.assign_to_row.view(T, k) >= 0).any(dim=1).sum().item())
     stages = {}
 
@@ -580,22 +702,20 @@ def main():
     for st in stages.values():
         st["rate"] = st["work"] / (st["ms"] * 1e-3) / (1e12 if st["kind"] == "flops" else 1e9)
         st["unit"] = "TFLOP/s" if st["kind"] == "flops" else "GB/s"
-    on_path = [n for n in stages if fp4 or n != "quantize_experts_fp4"]
-    dom = max(on_path, key=lambda n: stages[n]["ms"])
-    d = stages[dom]
-    if d["kind"] == "flops":
-        peak = PEAK_TFLOPS[args.precision]
-        roofline = {"kernel": dom, "bound": "mfma", "achieved": d["rate"], "peak": peak, "unit": "TFLOP/s",
-                    "frac": d["rate"] / peak, "traffic": None, "ms": d["ms"]}
-    else:
-        roofline = {"kernel": dom, "bound": "hbm", "achieved": d["rate"], "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                    "frac": d["rate"] / PEAK_HBM_GBS, "traffic": None, "ms": d["ms"]}
 
-    # measured HBM traffic of the dominant kernel, if a counter summary for this workload is committed
-    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")
+    # ---- roofline of the dominant kernel of the step: the gate/up GEMM as the layer call launches it (rows fetched
+    #      through row_to_assign), from the stage pass above
+    peak = PEAK_TFLOPS[args.precision]
+    gu_ms, dn_ms = layer_stages["gate_up"], layer_stages["down"]
+    gu_rate = 4.0 * rows * H * I / (gu_ms * 1e-3) / 1e12
+    dn_rate = 2.0 * rows * H * I / (dn_ms * 1e-3) / 1e12
+    kernel = f"ffn_gemm256_kernel<{str(fp4).lower()}, true, true>"
+    roofline = {"kernel": kernel, "what": "gate/up grouped GEMM + SwiGLU as launched by realb_layer_forward (activation rows fetched through row_to_assign)",
+                "bound": "mfma", "achieved": gu_rate, "peak": peak, "unit": "TFLOP/s", "frac": gu_rate / peak, "traffic": None, "ms": gu_ms}
+    traffic_file = os.path.join(ROOT, "profiles", "traffic.json")      # HBM bytes per launch from the committed counter runs, keyed by kernel
     if os.path.exists(traffic_file):
         with open(traffic_file) as f:
-            roofline["traffic"] = json.load(f).get(f"{args.workload}_{args.precision}_{dom}")
+            roofline["traffic"] = json.load(f).get(f"{args.workload}_{args.precision}:{kernel}")
     if args.calibrate_copy:
         src = torch.ones(128 << 20, dtype=torch.int32, device="cuda")
         dst = torch.empty_like(src)
@@ -604,17 +724,32 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    ffn_ms = stages["ffn_gate_up"]["ms"] + stages["ffn_down"]["ms"]
+    ffn_ms = gu_ms + dn_ms
     extra = {
         "rows_on_rank": rows,
+        "preroll_ms": round(preroll_ms, 1), "preroll_steps": preroll_steps,
         "grouped_gemm_tflops": ffn_flops / (ffn_ms * 1e-3) / 1e12,
-        "grouped_gemm_frac_of_peak": ffn_flops / (ffn_ms * 1e-3) / 1e12 / PEAK_TFLOPS[args.precision],
+        "grouped_gemm_frac_of_peak": ffn_flops / (ffn_ms * 1e-3) / 1e12 / peak,
+        "gate_up_frac_of_peak": gu_rate / peak, "down_tflops": dn_rate, "down_frac_of_peak": dn_rate / peak,
+        "down_frac_of_hbm": (rows * (2 * H + (I * 17 / 32 if fp4 else 2 * I)) / (dn_ms * 1e-3) / 1e9) / PEAK_HBM_GBS,
         "quantizer_gbs": stages["quantize_experts_fp4"]["rate"],
         "quantizer_frac_of_hbm": stages["quantize_experts_fp4"]["rate"] / PEAK_HBM_GBS,
         "layer_ms": ms_step,
-        "layer_ms_by_encode_mode": {k: round(v, 5) for k, v in by_mode.items()},
-        "stages_ms": {n: round(s["ms"], 5) for n, s in stages.items()},
+        "layer_ms_by_encode_mode": {k_: round(v, 5) for k_, v in by_mode.items()},
+        "layer_stages_ms": {n: round(v, 5) for n, v in layer_stages.items()},
+        "entry_point_ms": {n: round(st["ms"], 5) for n, st in stages.items()},
     }
+    if fp4 and mode == "prefetch":
+        extra["reserve_cus"] = lr.reserve
+    # ---- the other half of the metric ("BF16 vs FP4") and the Qwen-shaped layer, briefly, in the same run
+    if not args.no_compare and args.workload == "c2":
+        other = lr.brief(not fp4, "main" if fp4 else args.encode_mode)
+        extra["same_layer_" + ("bf16" if fp4 else "fp4")] = other
+        extra["fp4_speedup_over_bf16"] = (other["layer_ms"] / ms_step) if fp4 else (ms_step / other["layer_ms"])
+        lr3 = LayerRun("c3", args, torch, W, R, default_config)
+        extra["c3"] = {"fp4": lr3.brief(True, args.encode_mode), "bf16": lr3.brief(False, "main")}
+        extra["c3"]["fp4_speedup_over_bf16"] = extra["c3"]["bf16"]["layer_ms"] / extra["c3"]["fp4"]["layer_ms"]
+        lr3.close()
     result = {
         "metric": "grouped-GEMM TFLOP/s of the rank's SwiGLU FFN (6*R*H*I flop) over the whole rank-layer step",
         "value": ffn_flops / (ms_step * 1e-3) / 1e12, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps,
@@ -623,16 +758,16 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {cfg.E} experts top-{cfg.k}, {cfg.n_local} local, H={H} I={I}, "
                                f"T={T} tokens, {int(cfg.vision_frac * 100)}% vision, precision {args.precision} forced, "
-                               f"weight encoding mode {args.encode_mode}"},
+                               f"weight encoding mode {mode}"},
         "roofline": roofline,
         "extra": extra,
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(cfg, inp, fp4)
+        result["cpu_baseline"] = cpu_baseline(cfg, lr.inp, fp4)
     if args.detail:
         with open(args.detail, "w") as f:
             json.dump({"result": result, "stages": stages}, f, indent=1)
-    ctx.close()
+    lr.close()
     print(json.dumps(result))
 
 

@@ -81,7 +81,7 @@ const char* realb_last_error(void);
 
 /* Device memory, in bytes, that realb_create allocates for this configuration (the permutation's per-chunk
  * counters and the routing kernel's per-block partial histograms); besides it a context holds 8*D bytes of
- * pinned host memory, one stream and three events.  Host-only, no GPU needed; 0 for an unsupported shape
+ * pinned host memory, one stream and four events.  Host-only, no GPU needed; 0 for an unsupported shape
  * (realb_last_error says why). */
 size_t realb_workspace_bytes(const realb_config* cfg);
 
@@ -237,8 +237,19 @@ typedef struct {
                                                    2 = skipped (w13_q .. w2_s already hold this layer's encoded weights),
                                                    3 = speculative (realb_layer_forward only): issued on the side stream
                                                        BEFORE routing, so that it fills the wait for the host's decision;
-                                                       unused if the decision is BF16 */
+                                                       unused if the decision is BF16 (in modes 3 and 4 the activations
+                                                       of all T tokens are encoded there ahead of the decision as well),
+                                                   4 = prefetched: w13_q .. w2_s are being filled by the previous call's
+                                                       cross-layer prefetch (see next_w13 below); the GEMMs wait for it */
     long long max_rows;
+    /* cross-layer prefetch (optional, all NULL / 0 to disable): the NEXT layer's BF16 weights and the buffers that
+       receive their FP4 encoding.  The encoder for them is issued on the context's side stream right behind this
+       layer's gate/up GEMM launch and runs beside this layer's two GEMMs, which leave `reserve_cus` compute units
+       free for it (their persistent grids shrink by that many blocks).  The next call then passes those buffers as
+       w13_q .. w2_s with overlap = 4.  The buffers must differ from this call's w13_q .. w2_s. */
+    const void* next_w13; const void* next_w2;
+    uint8_t* next_w13_q; uint8_t* next_w13_s; uint8_t* next_w2_q; uint8_t* next_w2_s;
+    int reserve_cus;
     /* outputs / workspaces (caller-allocated) */
     int32_t* topk_ids; float* topk_w; int32_t* expert_cnt; int32_t* expert_vis;
     int32_t* rank_load; int32_t* rank_vis;
@@ -259,12 +270,32 @@ typedef struct {
 /* Runs the whole path for one rank on `stream`: route_stats -> select_precision
  * (host decision, one stream sync) -> [FP4 only: quantize_experts_fp4, on the
  * context's side stream when io->overlap, concurrent with] permute ->
- * grouped_moe_ffn -> combine.  The side stream is joined before the GEMMs. */
+ * grouped_moe_ffn -> combine.  The side stream is joined before the GEMMs.
+ * With next_w13 set, the next layer's weights are encoded on the side stream beside this layer's GEMMs
+ * (cross-layer form of the overlapping pipeline of Sec. "Overhead-Aware Pipeline Orchestration": the
+ * GEMMs are compute-bound and leave the memory system idle, as the dispatch does in the paper); that
+ * encoding is joined by the NEXT call (overlap = 4), or by realb_prefetch_join. */
 int realb_layer_forward(realb_ctx* ctx, realb_layer_io* io, void* stream);
 
 /* Runs permute .. combine for one rank with a precision already decided and
  * routing already computed (used to time simulated ranks one after the other). */
 int realb_rank_forward(realb_ctx* ctx, realb_layer_io* io, int prec, void* stream);
+
+/* Measurement aid: per-stage GPU time of the layer calls.  While enabled, realb_layer_forward and
+ * realb_rank_forward record timing events on the caller's stream at their stage boundaries (a few
+ * microseconds of overhead per call, so leave it off when timing whole steps); realb_stage_ms waits for
+ * the last call and returns, in milliseconds, how long each stage of THAT call took on the GPU:
+ *   [0] route_stats  [1] permutation indices  [2] host decision + weight encoding on the caller's stream
+ *   [3] gather / activation encoding  [4] gate/up GEMM  [5] down GEMM  [6] combine
+ * (realb_rank_forward: [0] is 0).  ms_host receives REALB_N_STAGES floats.  REALB_EINVAL if timing is
+ * off or no call has been made since it was switched on. */
+enum { REALB_N_STAGES = 7 };
+int realb_stage_timing(realb_ctx* ctx, int enable);
+int realb_stage_ms(realb_ctx* ctx, float* ms_host);
+
+/* Makes `stream` wait for the cross-layer prefetch issued by the last realb_layer_forward / realb_rank_forward
+ * call of this context (e.g. before the caller frees or reuses the next_* buffers without running the next layer). */
+int realb_prefetch_join(realb_ctx* ctx, void* stream);
 
 #ifdef __cplusplus
 }

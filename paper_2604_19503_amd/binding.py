@@ -17,7 +17,7 @@ EXPORTS = [
     "realb_quantize_rows_fp4", "realb_permute", "realb_grouped_moe_ffn", "realb_grouped_moe_ffn_gate_up",
     "realb_grouped_moe_ffn_down", "realb_set_gemm_tile", "realb_combine", "realb_layer_forward", "realb_rank_forward",
     "realb_quantize_rows_nvfp4", "realb_amax_bf16", "realb_route_stats_static",
-    "realb_workspace_bytes", "realb_scale_offset", "realb_scale_index_map",
+    "realb_workspace_bytes", "realb_scale_offset", "realb_scale_index_map", "realb_prefetch_join", "realb_stage_timing", "realb_stage_ms",
 ]
 
 
@@ -35,6 +35,8 @@ class LayerIO(C.Structure):
     _fields_ = [("logits", C.c_void_p), ("is_vision", C.c_void_p), ("x", C.c_void_p), ("T", C.c_int),
                 ("w13", C.c_void_p), ("w2", C.c_void_p), ("rank", C.c_int), ("force", C.c_int), ("overlap", C.c_int),
                 ("max_rows", C.c_longlong),
+                ("next_w13", C.c_void_p), ("next_w2", C.c_void_p), ("next_w13_q", C.c_void_p), ("next_w13_s", C.c_void_p),
+                ("next_w2_q", C.c_void_p), ("next_w2_s", C.c_void_p), ("reserve_cus", C.c_int),
                 ("topk_ids", C.c_void_p), ("topk_w", C.c_void_p), ("expert_cnt", C.c_void_p), ("expert_vis", C.c_void_p),
                 ("rank_load", C.c_void_p), ("rank_vis", C.c_void_p),
                 ("expert_offsets", C.c_void_p), ("row_to_assign", C.c_void_p), ("assign_to_row", C.c_void_p),
@@ -87,6 +89,9 @@ def load_library() -> C.CDLL:
     lib.realb_combine.argtypes = [vp, vp, vp, vp, C.c_int, vp, vp]
     lib.realb_layer_forward.argtypes = [vp, C.POINTER(LayerIO), vp]
     lib.realb_rank_forward.argtypes = [vp, C.POINTER(LayerIO), C.c_int, vp]
+    lib.realb_prefetch_join.argtypes = [vp, vp]
+    lib.realb_stage_timing.argtypes = [vp, C.c_int]
+    lib.realb_stage_ms.argtypes = [vp, vp]
     lib.realb_quantize_rows_nvfp4.argtypes = [vp, C.c_longlong, C.c_int, C.c_float, vp, vp, vp]
     lib.realb_amax_bf16.argtypes = [vp, C.c_longlong, vp, vp]
     _LIB = lib
@@ -231,6 +236,19 @@ class LayerBuffers:
         self.out = torch.empty((T, H), **bf)
 
 
+class WeightBuffers:
+    """One set of FP4 weight buffers (codes and K-step-tiled scales) for a rank's experts; two of them
+    serve the cross-layer prefetch as a ping-pong pair."""
+
+    def __init__(self, cfg: Config, device="cuda"):
+        nl, H, I = cfg.E // cfg.D, cfg.H, cfg.I
+        u8 = dict(dtype=torch.uint8, device=device)
+        self.w13_q = torch.empty((nl, 2 * I, H // 2), **u8)
+        self.w13_s = torch.empty((nl, 2 * I, H // 32), **u8)
+        self.w2_q = torch.empty((nl, H, I // 2), **u8)
+        self.w2_s = torch.empty((nl, H, I // 32), **u8)
+
+
 class Context:
     """Owns a realb_ctx.  Methods mirror the C entry points one to one."""
 
@@ -303,7 +321,8 @@ class Context:
     def make_io(self, logits, is_vision, x, w13, w2, b: LayerBuffers, rank: int, force: int = FORCE_NONE,
                 overlap=True) -> LayerIO:
         """overlap: 0/False = weight encoding on the call's stream, 1/True = on the context's side stream,
-        2 = skipped (the buffers already hold this layer's encoded weights)."""
+        2 = skipped (the buffers already hold this layer's encoded weights), 3 = speculative (before routing),
+        4 = prefetched by the previous call (see set_prefetch)."""
         io = LayerIO()
         g = lambda t: None if t is None else t.data_ptr()
         io.logits, io.is_vision, io.x, io.T = g(logits), g(is_vision), g(x), x.shape[0]
@@ -318,6 +337,33 @@ class Context:
     def layer_forward(self, io: LayerIO, stream=None):
         _check(self.lib.realb_layer_forward(self._h, C.byref(io), _stream(stream)))
         return int(io.prec_host[io.rank])
+
+    def set_prefetch(self, io: LayerIO, next_w13, next_w2, wbuf: "WeightBuffers", reserve_cus: int):
+        """Arms the cross-layer prefetch of a layer call: the next layer's weights are encoded into wbuf beside
+        this layer's GEMMs, which leave reserve_cus compute units free."""
+        io.next_w13, io.next_w2 = next_w13.data_ptr(), next_w2.data_ptr()
+        io.next_w13_q, io.next_w13_s, io.next_w2_q, io.next_w2_s = (t.data_ptr() for t in (wbuf.w13_q, wbuf.w13_s, wbuf.w2_q, wbuf.w2_s))
+        io.reserve_cus = int(reserve_cus)
+        io._keep_next = (next_w13, next_w2, wbuf)
+
+    def use_weight_buffers(self, io: LayerIO, wbuf: "WeightBuffers"):
+        """Points a layer call's FP4 weight buffers at wbuf (instead of the LayerBuffers' own)."""
+        io.w13_q, io.w13_s, io.w2_q, io.w2_s = (t.data_ptr() for t in (wbuf.w13_q, wbuf.w13_s, wbuf.w2_q, wbuf.w2_s))
+        io._keep_w = wbuf
+
+    STAGES = ("route_stats", "permute_indices", "decision_and_encode", "gather", "gate_up", "down", "combine")
+
+    def stage_timing(self, enable: bool):
+        _check(self.lib.realb_stage_timing(self._h, int(bool(enable))))
+
+    def stage_ms(self) -> dict:
+        """realb_stage_ms: GPU milliseconds of each stage of the last layer call (waits for it)."""
+        ms = (C.c_float * len(self.STAGES))()
+        _check(self.lib.realb_stage_ms(self._h, ms))
+        return dict(zip(self.STAGES, (float(v) for v in ms)))
+
+    def prefetch_join(self, stream=None):
+        _check(self.lib.realb_prefetch_join(self._h, _stream(stream)))
 
     def rank_forward(self, io: LayerIO, prec: int, stream=None):
         _check(self.lib.realb_rank_forward(self._h, C.byref(io), prec, _stream(stream)))

@@ -26,6 +26,13 @@ struct Ctx {
     int32_t* stats_host;   // [2*D]
     hipStream_t side;      // side stream for the weight encoder
     hipEvent_t ev_fork, ev_join;
+    hipEvent_t ev_prefetch;   // end of the last cross-layer prefetch on the side stream
+    bool prefetch_pending;    // ev_prefetch has been recorded and not yet been waited for by a caller's stream
+    int gemm_reserve;         // compute units the grouped GEMMs' persistent grids leave free (set around a prefetching call)
+    // optional per-stage timing of the layer calls (realb_stage_timing): events recorded on the caller's stream
+    bool stage_timing;
+    bool stage_valid;      // a whole layer call has recorded all boundaries since timing was switched on
+    hipEvent_t stage_ev[REALB_N_STAGES + 1];
     hipEvent_t ev_stats;   // recorded behind the histogram reduce: the host's cue that the routing statistics are in stats_host
 };
 
@@ -43,6 +50,9 @@ int launch_gate_up_fp4_gather(Ctx* c, const int32_t* expert_offsets, int n_local
                               const uint8_t* w13_s, uint8_t* h_q, uint8_t* h_s, hipStream_t s);
 int permute_gather(Ctx* c, const void* x, const int32_t* assign_to_row, int T, int prec, void* x_perm, uint8_t* x_q,
                    uint8_t* x_s, hipStream_t s, int token_major);
+// BF16 -> MXFP4 encoder on one matrix [rows0, K0], or two when rows1 > 0, in a single launch.
+int launch_quantize_flat(const void* src0, long long rows0, int K0, uint8_t* q0, uint8_t* s0,
+                         const void* src1, long long rows1, int K1, uint8_t* q1, uint8_t* s1, hipStream_t stream);
 int hip_fail(hipError_t e, const char* what);
 // Address (on the current device) of the file-scope scratch array of realb_route_stats_static and the device's CU
 // count; looked up once per device and cached.  Either output may be NULL.
@@ -58,6 +68,11 @@ int static_scratch_lookup(int32_t** ptr, int* num_cus);
     do {                                                                       \
         if (!(cond)) { ::realb::set_error(__VA_ARGS__); return (code); }       \
     } while (0)
+
+// Stage boundary i of a layer call (no-op unless stage timing is on).
+inline void stage_mark(Ctx* c, hipStream_t s, int i) {
+    if (c->stage_timing) (void)hipEventRecord(c->stage_ev[i], s);
+}
 
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 inline int ceil_div(long long a, long long b) { return (int)((a + b - 1) / b); }

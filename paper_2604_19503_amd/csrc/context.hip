@@ -109,7 +109,8 @@ int realb_create(const realb_config* cfg, realb_ctx** out) {
     c->cfg = *cfg;
     c->n_local = cfg->E / cfg->D;
     c->M = cfg->M_init;
-    c->wave_cnt = nullptr; c->hist_part = nullptr; c->stats_host = nullptr; c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr; c->ev_stats = nullptr;
+    c->wave_cnt = nullptr; c->hist_part = nullptr; c->stats_host = nullptr; c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr; c->ev_stats = nullptr; c->ev_prefetch = nullptr; c->prefetch_pending = false; c->gemm_reserve = 0; c->stage_timing = false; c->stage_valid = false;
+    for (auto& ev : c->stage_ev) ev = nullptr;
     hipError_t e = hipGetDevice(&c->device);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&c->num_cus, hipDeviceAttributeMultiprocessorCount, c->device);
     c->n_chunks_max = n_chunks_max(cfg);
@@ -120,6 +121,7 @@ int realb_create(const realb_config* cfg, realb_ctx** out) {
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_stats, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_prefetch, hipEventDisableTiming);
     if (e != hipSuccess) {
         realb_destroy(reinterpret_cast<realb_ctx*>(c));
         return hip_fail(e, "realb_create");
@@ -143,6 +145,9 @@ int realb_destroy(realb_ctx* ctx) {
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
     if (c->ev_stats) (void)hipEventDestroy(c->ev_stats);
+    if (c->ev_prefetch) (void)hipEventDestroy(c->ev_prefetch);
+    for (auto& ev : c->stage_ev)
+        if (ev) (void)hipEventDestroy(ev);
     if (c->side) (void)hipStreamDestroy(c->side);
     delete c;
     return REALB_OK;
@@ -164,6 +169,27 @@ int realb_scale_index_map(long long rows, int K, int64_t* idx_host) {
     const int nb = K / 32, KD = K >> 7;
     for (long long r = 0; r < rows; ++r)
         for (int kb = 0; kb < nb; ++kb) idx_host[r * nb + kb] = (int64_t)scale_byte_offset(r, kb, KD);
+    return REALB_OK;
+}
+
+int realb_stage_timing(realb_ctx* ctx, int enable) {
+    REALB_REQUIRE(ctx != nullptr, REALB_EINVAL, "ctx is NULL");
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    if (enable)
+        for (auto& ev : c->stage_ev)
+            if (!ev) REALB_HIP(hipEventCreate(&ev));
+    c->stage_timing = false;                       // no valid measurement until the next layer call
+    c->stage_valid = false;
+    c->stage_timing = enable != 0;
+    return REALB_OK;
+}
+
+int realb_stage_ms(realb_ctx* ctx, float* ms_host) {
+    REALB_REQUIRE(ctx && ms_host, REALB_EINVAL, "NULL argument");
+    Ctx* c = reinterpret_cast<Ctx*>(ctx);
+    REALB_REQUIRE(c->stage_timing && c->stage_valid, REALB_EINVAL, "stage timing is off, or no layer call since it was switched on");
+    REALB_HIP(hipEventSynchronize(c->stage_ev[REALB_N_STAGES]));
+    for (int i = 0; i < REALB_N_STAGES; ++i) REALB_HIP(hipEventElapsedTime(&ms_host[i], c->stage_ev[i], c->stage_ev[i + 1]));
     return REALB_OK;
 }
 

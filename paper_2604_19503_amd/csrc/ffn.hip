@@ -80,9 +80,23 @@ struct GemmParams {
     int w_rows;              // weight rows per expert (2I or H)
     int n_out;               // output columns (I or H)
     int n_tiles_n;           // column tiles (I/GC or H/BNW)
-    const int32_t* row_src;  // gathering gate/up GEMM only: row_to_assign; row r's activations are A[row_src[r] / src_div]
-    int src_div;             //                              (experts per token)
+    const int32_t* row_src;  // gathering gate/up GEMM only: row_to_assign; row r's activations are A[row_src[r] / k]
+    uint32_t src_magic;      //   a / k == (a * src_magic) >> src_shift for 0 <= a < 2^31  (k = experts per token)
+    int src_shift;
 };
+
+// Exact division of 0 <= a < 2^31 by a small constant k through one multiplication: with s = ceil(log2 k) and
+// m = floor(2^(31+s) / k) + 1 < 2^32, the excess m*k - 2^(31+s) is at most k <= 2^s, so a*m / 2^(31+s) exceeds
+// a/k by less than 1/k and the floors agree.
+static void division_magic(int k, uint32_t* magic, int* shift) {
+    int s = 0;
+    while ((1 << s) < k) ++s;
+    *magic = (uint32_t)((1ull << (31 + s)) / (unsigned)k + 1);
+    *shift = 31 + s;
+}
+__device__ __forceinline__ int div_by_magic(int a, uint32_t magic, int shift) {
+    return (int)(((unsigned long long)(uint32_t)a * magic) >> shift);
+}
 
 // acc += W_tile (A operand, 32 weight rows) x X_tile^T (B operand, 32 activation rows)
 template <bool FP4, int OPSEL>
@@ -154,12 +168,10 @@ __device__ __forceinline__ bool stream_output(const GemmParams& p) {
 // store rate measured.  `base` points at column 0 of tile row 0; rows >= rows_left are not written.
 // NT: non-temporal stores.  They drain faster, but the output then bypasses the memory-side cache, from
 // which the next kernel would otherwise read it back: worth it only for outputs too large to stay there.
-template <bool NT>
-__device__ __forceinline__ void store_tile_rows(uint8_t* base, size_t row_pitch, int lane, int rows_left,
-                                                const u32x4_t& c0, const u32x4_t& c1) {
-    const int li = lane & 31, half = lane >> 5;
+// Prepares the two store registers of store_tile_rows: ra = this lane's 16-byte piece of the even row of its
+// pair, rb = of the odd row.
+__device__ __forceinline__ void swap_halves(int lane, const u32x4_t& c0, const u32x4_t& c1, u32x4_t& ra, u32x4_t& rb) {
     const bool odd = lane & 1;
-    u32x4_t ra, rb;
     const uint32_t a0[4] = {c0.x, c0.y, c0.z, c0.w}, a1[4] = {c1.x, c1.y, c1.z, c1.w};
     uint32_t xa[4], xb[4];
 #pragma unroll
@@ -171,15 +183,42 @@ __device__ __forceinline__ void store_tile_rows(uint8_t* base, size_t row_pitch,
     }
     ra = u32x4_t{xa[0], xa[1], xa[2], xa[3]};
     rb = u32x4_t{xb[0], xb[1], xb[2], xb[3]};
+}
+template <bool NT>
+__device__ __forceinline__ void store16(uint8_t* dst, const u32x4_t& v, bool on) {
+    if constexpr (NT) {
+        if (on) __builtin_nontemporal_store(v, reinterpret_cast<u32x4_t*>(dst));
+    } else {
+        if (on) *reinterpret_cast<u32x4_t*>(dst) = v;
+    }
+}
+template <bool NT>
+__device__ __forceinline__ void store_tile_rows(uint8_t* base, size_t row_pitch, int lane, int rows_left,
+                                                const u32x4_t& c0, const u32x4_t& c1) {
+    const int li = lane & 31, half = lane >> 5;
+    u32x4_t ra, rb;
+    swap_halves(lane, c0, c1, ra, rb);
     const int row_a = li & ~1;
     uint8_t* dst = base + (size_t)row_a * row_pitch + (half * 2 + (lane & 1)) * 16;
-    if constexpr (NT) {
-        if (row_a < rows_left) __builtin_nontemporal_store(ra, reinterpret_cast<u32x4_t*>(dst));
-        if (row_a + 1 < rows_left) __builtin_nontemporal_store(rb, reinterpret_cast<u32x4_t*>(dst + row_pitch));
-    } else {
-        if (row_a < rows_left) *reinterpret_cast<u32x4_t*>(dst) = ra;
-        if (row_a + 1 < rows_left) *reinterpret_cast<u32x4_t*>(dst + row_pitch) = rb;
-    }
+    store16<NT>(dst, ra, row_a < rows_left);
+    store16<NT>(dst + row_pitch, rb, row_a + 1 < rows_left);
+}
+// Two neighbouring 32-column tiles of the same 32 rows (128 contiguous bytes per row).  The two 64-byte halves of
+// a row's line are written by consecutive instructions, so that they reach the memory side together (streamed
+// stores of half lines that arrive far apart cost extra write traffic).
+template <bool NT>
+__device__ __forceinline__ void store_tile_pair(uint8_t* base, size_t row_pitch, int lane, int rows_left, const u32x4_t& p0,
+                                                const u32x4_t& p1, const u32x4_t& q0, const u32x4_t& q1) {
+    const int li = lane & 31, half = lane >> 5;
+    u32x4_t pa, pb, qa, qb;
+    swap_halves(lane, p0, p1, pa, pb);
+    swap_halves(lane, q0, q1, qa, qb);
+    const int row_a = li & ~1;
+    uint8_t* dst = base + (size_t)row_a * row_pitch + (half * 2 + (lane & 1)) * 16;
+    store16<NT>(dst, pa, row_a < rows_left);
+    store16<NT>(dst + 64, qa, row_a < rows_left);
+    store16<NT>(dst + row_pitch, pb, row_a + 1 < rows_left);
+    store16<NT>(dst + row_pitch + 64, qb, row_a + 1 < rows_left);
 }
 
 // Epilogue, straight from registers.  acc[mt][t][r] belongs to activation row wm*128 + mt*32 + li
@@ -229,15 +268,20 @@ __device__ __forceinline__ void epilogue(const GemmParams& p, v16f_t (&acc)[4][W
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) {
             const int tile_row0 = wm * 128 + mt * 32;
+            auto lo8 = [&](int t) __attribute__((always_inline)) {
+                return u32x4_t{pack_bf16x2(acc[mt][t][0], acc[mt][t][1]), pack_bf16x2(acc[mt][t][2], acc[mt][t][3]),
+                               pack_bf16x2(acc[mt][t][4], acc[mt][t][5]), pack_bf16x2(acc[mt][t][6], acc[mt][t][7])};
+            };
+            auto hi8 = [&](int t) __attribute__((always_inline)) {
+                return u32x4_t{pack_bf16x2(acc[mt][t][8], acc[mt][t][9]), pack_bf16x2(acc[mt][t][10], acc[mt][t][11]),
+                               pack_bf16x2(acc[mt][t][12], acc[mt][t][13]), pack_bf16x2(acc[mt][t][14], acc[mt][t][15])};
+            };
+            static_assert(WN % 2 == 0, "column tiles are stored in pairs");
 #pragma unroll
-            for (int t = 0; t < WN; ++t) {
+            for (int t = 0; t < WN; t += 2) {
                 const int col0 = n0 + wn * WN * 32 + t * 32;
-                store_tile_rows<NT>(p.out + ((size_t)(row0 + tile_row0) * p.n_out + col0) * 2, (size_t)p.n_out * 2, lane,
-                                rows_valid - tile_row0,
-                                u32x4_t{pack_bf16x2(acc[mt][t][0], acc[mt][t][1]), pack_bf16x2(acc[mt][t][2], acc[mt][t][3]),
-                                        pack_bf16x2(acc[mt][t][4], acc[mt][t][5]), pack_bf16x2(acc[mt][t][6], acc[mt][t][7])},
-                                u32x4_t{pack_bf16x2(acc[mt][t][8], acc[mt][t][9]), pack_bf16x2(acc[mt][t][10], acc[mt][t][11]),
-                                        pack_bf16x2(acc[mt][t][12], acc[mt][t][13]), pack_bf16x2(acc[mt][t][14], acc[mt][t][15])});
+                store_tile_pair<NT>(p.out + ((size_t)(row0 + tile_row0) * p.n_out + col0) * 2, (size_t)p.n_out * 2, lane,
+                                    rows_valid - tile_row0, lo8(t), hi8(t), lo8(t + 1), hi8(t + 1));
             }
         }
     }
@@ -465,7 +509,9 @@ constexpr int SC_BASE = 2 * STAGE;         // FP4: scale staging, per stage [512
 constexpr int SC_STAGE = 512 * 8;
 constexpr int SC_W = 256 * 8;
 constexpr int TAB_BASE = SC_BASE + 2 * SC_STAGE;   // expert table, 3 x 64 ints
-constexpr int LDS_BYTES = TAB_BASE + 3 * 64 * 4;
+constexpr int TOK_BASE = TAB_BASE + 3 * 64 * 4;    // gathering kernel: row_to_assign entries of a tile, two buffers x 8 waves x 64 ints
+constexpr int TOK_BUF = 8 * 64 * 4;
+constexpr int LDS_BYTES = TOK_BASE + 2 * TOK_BUF;
 }  // namespace t256
 
 __device__ __forceinline__ void lds_dma16(const uint8_t* g, uint8_t* l) {
@@ -561,22 +607,33 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
     const uint8_t* b_tile = nullptr;
 
     TileInfo ti = decode(tile);
+    // GATHER: the row_to_assign entries of a tile's rows are brought into LDS one tile ahead (a wave fetches the
+    // entries of its own 32 rows with one direct-to-LDS transfer and later reads back only what it fetched), so
+    // that switching tiles never waits for global memory: a register load at the switch would stall the producer
+    // for a full memory latency, behind every transfer in flight.
+    int tokbuf = 0;
+    auto fetch_tokens = [&](const TileInfo& t, int buf) __attribute__((always_inline)) {
+        if constexpr (GATHER) {
+            const int row0 = __builtin_amdgcn_readfirstlane(t.row0), rows = __builtin_amdgcn_readfirstlane(t.seg_hi - t.row0);
+            const int r = row0 + min(wave * 32 + (lane & 31), rows - 1);          // rows past the segment: its last row again
+            lds_dma4(reinterpret_cast<const uint32_t*>(p.row_src) + r, smem + TOK_BASE + buf * TOK_BUF + wave * 256);
+        }
+    };
     auto setup_src = [&](const TileInfo& t) __attribute__((always_inline)) {
         const int row0 = __builtin_amdgcn_readfirstlane(t.row0), rows = __builtin_amdgcn_readfirstlane(t.seg_hi - t.row0);
         const int e = __builtin_amdgcn_readfirstlane(t.e), n0 = __builtin_amdgcn_readfirstlane(t.n0);
         a_tile = GATHER ? p.A : p.A + (size_t)row0 * rowbytes;
         b_tile = p.W + ((size_t)e * p.w_rows + n0) * rowbytes;
         a_last = rows - 1;
+        const int* toks = reinterpret_cast<const int*>(smem + TOK_BASE + tokbuf * TOK_BUF) + wave * 64;   // this tile's entries (GATHER)
         if constexpr (GATHER) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const int r = row0 + min(wave * 32 + j * 8 + prow, rows - 1);
-                a_goff[j] = (uint32_t)(p.row_src[r] / p.src_div) * rowbytes + part16(j & 1);
-            }
+            for (int j = 0; j < 4; ++j)
+                a_goff[j] = (uint32_t)div_by_magic(toks[j * 8 + prow], p.src_magic, p.src_shift) * rowbytes + part16(j & 1);
         }
         if constexpr (FP4) {
             int gr = row0 + min(srow, rows - 1);
-            if constexpr (GATHER) gr = p.row_src[gr] / p.src_div;      // the token that holds this row's codes and scales
+            if constexpr (GATHER) gr = div_by_magic(toks[lane >> 1], p.src_magic, p.src_shift);   // the token that holds this row's codes and scales
             sa_idx = ((gr >> 5) * kd) * 32 + (gr & 31);
             const int br = (srow & ~31) | w_row_of_lane(srow & 31);
             const int wr = e * p.w_rows + w_tile_row<GATEUP, 128>(br, n0, I_up);
@@ -617,10 +674,19 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
             pk = 0;
             if (ptile + nslots < tile_hi) {
                 ptile += nslots;
+                if constexpr (GATHER) tokbuf ^= 1;                     // fetched while the previous tile was being produced
                 setup_src(decode(ptile));
+                if constexpr (GATHER) {
+                    if (ptile + nslots < tile_hi) fetch_tokens(decode(ptile + nslots), tokbuf ^ 1);
+                }
             }
         }
     };
+    if constexpr (GATHER) {
+        fetch_tokens(ti, 0);
+        if (tile + nslots < tile_hi) fetch_tokens(decode(tile + nslots), 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
     setup_src(ti);
 #pragma unroll
     for (int op = 0; op < 10; ++op) issue(op, 0, 0);
@@ -765,7 +831,9 @@ static int launch_gemm256(GemmParams p, long long max_rows, const Ctx* c, hipStr
     }
     const long long m_tiles_max = (max_rows + BM - 1) / BM + p.n_local;
     const long long total_max = m_tiles_max * p.n_tiles_n;
-    const long long slots = 8ll * (((long long)num_cus + 7) / 8);          // one persistent block per CU, multiple of 8 (XCDs)
+    // one persistent block per CU, a multiple of 8 (XCDs); a prefetching layer call leaves some CUs to the weight encoder
+    const long long avail = (long long)num_cus - c->gemm_reserve;
+    const long long slots = avail >= 16 ? 8ll * (c->gemm_reserve > 0 ? avail / 8 : (avail + 7) / 8) : 8;
     const long long grid = total_max < slots ? 8 * ((total_max + 7) / 8) : slots;
     hipLaunchKernelGGL((ffn_gemm256_kernel<FP4, GATEUP, GATHER>), dim3((unsigned)grid), dim3(512), lds, s, p);
     REALB_HIP(hipGetLastError());
@@ -828,7 +896,8 @@ int launch_gate_up_bf16_gather(Ctx* c, const int32_t* expert_offsets, int n_loca
     const int H = c->cfg.H, I = c->cfg.I;
     if (!gate_up_gather_supported(c, T, false)) return REALB_ESHAPE;
     GemmParams g{(const uint8_t*)x, nullptr, (const uint8_t*)w13, nullptr, (uint8_t*)h_mid, nullptr, expert_offsets, n_local,
-                 H, 2 * I, I, 0, row_to_assign, c->cfg.k};
+                 H, 2 * I, I, 0, row_to_assign, 0, 0};
+    division_magic(c->cfg.k, &g.src_magic, &g.src_shift);
     return launch_gemm256<false, true, true>(g, max_rows, c, s);
 }
 
@@ -838,7 +907,8 @@ int launch_gate_up_fp4_gather(Ctx* c, const int32_t* expert_offsets, int n_local
                               const uint8_t* w13_s, uint8_t* h_q, uint8_t* h_s, hipStream_t s) {
     const int H = c->cfg.H, I = c->cfg.I;
     if (!gate_up_gather_supported(c, T, true)) return REALB_ESHAPE;
-    GemmParams g{x_q, x_s, w13_q, w13_s, h_q, h_s, expert_offsets, n_local, H, 2 * I, I, 0, row_to_assign, c->cfg.k};
+    GemmParams g{x_q, x_s, w13_q, w13_s, h_q, h_s, expert_offsets, n_local, H, 2 * I, I, 0, row_to_assign, 0, 0};
+    division_magic(c->cfg.k, &g.src_magic, &g.src_shift);
     return launch_gemm256<true, true, true>(g, max_rows, c, s);
 }
 
@@ -867,8 +937,8 @@ static int ffn_stages(realb_ctx* ctx, int prec, int stages, const int32_t* exper
                   "NULL scale tensor on the FP4 path");
     const int H = c->cfg.H, I = c->cfg.I;
     hipStream_t s = as_stream(stream);
-    GemmParams g1{(const uint8_t*)x, x_s, (const uint8_t*)w13, w13_s, (uint8_t*)h_mid, h_s, expert_offsets, n_local, H, 2 * I, I, 0, nullptr, 1};
-    GemmParams g2{(const uint8_t*)h_mid, h_s, (const uint8_t*)w2, w2_s, (uint8_t*)y_rows, nullptr, expert_offsets, n_local, I, H, H, 0, nullptr, 1};
+    GemmParams g1{(const uint8_t*)x, x_s, (const uint8_t*)w13, w13_s, (uint8_t*)h_mid, h_s, expert_offsets, n_local, H, 2 * I, I, 0, nullptr, 0, 0};
+    GemmParams g2{(const uint8_t*)h_mid, h_s, (const uint8_t*)w2, w2_s, (uint8_t*)y_rows, nullptr, expert_offsets, n_local, I, H, H, 0, nullptr, 0, 0};
     int rc = REALB_OK;
     if (prec == REALB_FP4) {
         if (s1) rc = launch_gemm<true, true>(g1, max_rows, c, s);

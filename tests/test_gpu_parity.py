@@ -392,6 +392,79 @@ def test_fused_gather_layer_equals_step_calls_for_odd_batch_sizes(R, T):
     ctx.close()
 
 
+@pytest.mark.parametrize("reserve", [0, 8, 40])
+def test_cross_layer_prefetch_pipeline_is_bit_identical(R, reserve):
+    """Four layers with distinct weights run as a pipeline: every layer call also encodes the NEXT layer's weights
+    on the side stream beside its own GEMMs (which leave `reserve` compute units free) into the other buffer set
+    of a ping-pong pair, and the next call consumes them (overlap = 4).  Rows, outputs and weight codes must be
+    those of the plain calls, bit for bit, for both the layer call and the rank call, and a BF16 layer in between
+    must neither disturb nor lose a prefetch."""
+    from paper_2604_19503_amd.binding import default_config
+    cfg = W.scaled(W.CONFIGS["c2"], T=3000, H=512, I=384)
+    rcfg = default_config(cfg.T, cfg.E, cfg.k, cfg.D, cfg.H, cfg.I)
+    ctx = R.Context(rcfg)
+    inp = W.gen_layer(cfg, 21)
+    x = R.bf16_from_bits(inp["x"])
+    lg = torch.from_numpy(inp["logits"]).cuda(); isv = torch.from_numpy(inp["is_vision"]).cuda()
+    L = 4
+    ws = [tuple(R.bf16_from_bits(a) for a in W.gen_weights(cfg, 300 + l)) for l in range(L)]
+    precs = [R.FP4, R.FP4, R.BF16, R.FP4]
+    # reference: plain calls, encoder on the call's stream
+    ref = []
+    b = R.LayerBuffers(rcfg, cfg.T)
+    for l in range(L):
+        io = ctx.make_io(lg, isv, x, ws[l][0], ws[l][1], b, cfg.rank, force=precs[l], overlap=0)
+        assert ctx.layer_forward(io) == precs[l]
+        _sync()
+        Rr = int(b.expert_offsets[-1])
+        ref.append((b.out.clone(), b.y_rows[:Rr].clone(), b.w13_q.clone(), b.w13_s.clone(), b.w2_q.clone(), b.w2_s.clone()))
+    for use_rank_call in (False, True):
+        _say(f"prefetch pipeline reserve={reserve} rank_call={use_rank_call}")
+        pair = [R.WeightBuffers(rcfg), R.WeightBuffers(rcfg)]
+        for wb in pair:
+            for t in (wb.w13_q, wb.w13_s, wb.w2_q, wb.w2_s):
+                t.fill_(0xEE)
+        b2 = R.LayerBuffers(rcfg, cfg.T)
+        if use_rank_call:
+            ctx.route_stats(lg, isv, b2)
+        outs = []
+        for l in range(L):
+            cur, nxt = pair[l & 1], pair[(l + 1) & 1]
+            # layer 0 has nobody to prefetch for it: it encodes on its own stream
+            io = ctx.make_io(lg, isv, x, ws[l][0], ws[l][1], b2, cfg.rank, force=precs[l], overlap=0 if l == 0 else 4)
+            ctx.use_weight_buffers(io, cur)
+            if l + 1 < L:
+                ctx.set_prefetch(io, ws[l + 1][0], ws[l + 1][1], nxt, reserve)
+            b2.out.fill_(float("nan"))
+            if use_rank_call:
+                ctx.rank_forward(io, precs[l])
+            else:
+                assert ctx.layer_forward(io) == precs[l]
+            outs.append((b2.out.clone(), b2.y_rows[:int(ref[l][1].shape[0])].clone()))      # stream-ordered copies, no host sync in the pipeline
+        ctx.prefetch_join()
+        _sync()
+        for l in range(L):
+            assert torch.equal(outs[l][0].view(torch.int16), ref[l][0].view(torch.int16)), l
+            assert torch.equal(outs[l][1].view(torch.int16), ref[l][1].view(torch.int16)), l
+        # layer 3's weights were prefetched into pair[1] and consumed there
+        assert torch.equal(pair[1].w13_q, ref[3][2]) and torch.equal(pair[1].w13_s, ref[3][3])
+        assert torch.equal(pair[1].w2_q, ref[3][4]) and torch.equal(pair[1].w2_s, ref[3][5])
+        # the BF16 layer's weights were prefetched all the same: check them against the encoder called directly
+        b3 = R.LayerBuffers(rcfg, cfg.T)
+        ctx.quantize_experts_fp4(ws[2][0], ws[2][1], b3)
+        _sync()
+        assert torch.equal(pair[0].w13_q, b3.w13_q) and torch.equal(pair[0].w2_s, b3.w2_s)
+    # arguments: prefetch into the buffers in use is refused
+    io = ctx.make_io(lg, isv, x, ws[0][0], ws[0][1], b, cfg.rank, force=R.FP4, overlap=0)
+    own = R.WeightBuffers(rcfg)
+    own.w13_q, own.w13_s, own.w2_q, own.w2_s = b.w13_q, b.w13_s, b.w2_q, b.w2_s
+    ctx.set_prefetch(io, ws[1][0], ws[1][1], own, 8)
+    with pytest.raises(R.RealbError):
+        ctx.layer_forward(io)
+    _sync()
+    ctx.close()
+
+
 # ---------------------------------------------------------------------------- edge cases
 def test_edge_empty_batch_and_empty_rank_and_empty_expert(R):
     from paper_2604_19503_amd.binding import default_config
