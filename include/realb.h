@@ -285,7 +285,8 @@ int realb_rank_forward(realb_ctx* ctx, realb_layer_io* io, int prec, void* strea
  * realb_rank_forward record timing events on the caller's stream at their stage boundaries (a few
  * microseconds of overhead per call, so leave it off when timing whole steps); realb_stage_ms waits for
  * the last call and returns, in milliseconds, how long each stage of THAT call took on the GPU:
- *   [0] route_stats  [1] permutation indices  [2] host decision + weight encoding on the caller's stream
+ *   [0] route_stats  [1] permutation indices (realb_layer_forward interleaves the two groups of kernels and reports
+ *   their sum under [0])  [2] host decision + weight encoding on the caller's stream
  *   [3] gather / activation encoding  [4] gate/up GEMM  [5] down GEMM  [6] combine
  * (realb_rank_forward: [0] is 0).  ms_host receives REALB_N_STAGES floats.  REALB_EINVAL if timing is
  * off or no call has been made since it was switched on. */

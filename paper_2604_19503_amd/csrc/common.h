@@ -48,6 +48,10 @@ bool gate_up_gather_supported(const Ctx* c, int T, bool fp4);
 int launch_gate_up_fp4_gather(Ctx* c, const int32_t* expert_offsets, int n_local, long long max_rows, const uint8_t* x_q,
                               const uint8_t* x_s, int T, const int32_t* row_to_assign, const uint8_t* w13_q,
                               const uint8_t* w13_s, uint8_t* h_q, uint8_t* h_s, hipStream_t s);
+int route_topk_only(Ctx* c, const float* logits, const uint8_t* is_vision, int T, int32_t* topk_ids, float* topk_w, hipStream_t s);
+int route_and_index(Ctx* c, const float* logits, const uint8_t* is_vision, int T, int rank, long long max_rows, int32_t* topk_ids,
+                    float* topk_w, int32_t* expert_cnt, int32_t* expert_vis, int32_t* rank_load, int32_t* rank_vis,
+                    int32_t* expert_offsets, int32_t* row_to_assign, int32_t* assign_to_row, hipEvent_t stats_ready, hipStream_t s);
 int permute_gather(Ctx* c, const void* x, const int32_t* assign_to_row, int T, int prec, void* x_perm, uint8_t* x_q,
                    uint8_t* x_s, hipStream_t s, int token_major);
 // BF16 -> MXFP4 encoder on one matrix [rows0, K0], or two when rows1 > 0, in a single launch.

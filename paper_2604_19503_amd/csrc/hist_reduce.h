@@ -1,0 +1,53 @@
+// One-block reduction of the routing kernel's per-block partial histograms, shared by the stand-alone
+// reduce kernel and by the layer call's fused reduce + scan launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace realb {
+
+// Adds up the blocks' partial histograms and the per-rank sums (also written to the context's pinned
+// host buffer, which realb_layer_forward reads after one stream synchronisation) (a separate launch: the kernel
+// boundary makes the partials of all XCDs visible).  Thread layout: counter c = tid % CW,
+// slice = tid / CW; each slice walks its share of the partials, LDS atomics merge the slices.
+// tot: 2*E ints of LDS.
+__device__ __forceinline__ void hist_reduce_body(int32_t* tot, const int32_t* __restrict__ hist_part, int n_part, int E, int D,
+                                                 int32_t* __restrict__ expert_cnt, int32_t* __restrict__ expert_vis,
+                                                 int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis,
+                                                 int32_t* __restrict__ stats_host) {
+    const int C2 = 2 * E;
+    for (int i = threadIdx.x; i < C2; i += blockDim.x) tot[i] = 0;
+    __syncthreads();
+    int cw = 1;
+    while (cw < C2) cw <<= 1;                         // counters per slice row, power of two, <= 1024
+    const int n_slices = blockDim.x / cw;
+    const int c = threadIdx.x % cw, slice = threadIdx.x / cw;
+    if (c < C2 && slice < n_slices) {
+        int sum = 0;
+        int b = slice;
+        for (; b + 31 * n_slices < n_part; b += 32 * n_slices) {       // 32 independent loads in flight per thread
+            int v[32];
+#pragma unroll
+            for (int i = 0; i < 32; ++i) v[i] = hist_part[(size_t)(b + i * n_slices) * C2 + c];
+#pragma unroll
+            for (int i = 0; i < 32; ++i) sum += v[i];
+        }
+        for (; b < n_part; b += n_slices) sum += hist_part[(size_t)b * C2 + c];
+        if (sum) atomicAdd(&tot[c], sum);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < E; i += blockDim.x) { expert_cnt[i] = tot[i]; expert_vis[i] = tot[E + i]; }
+    const int n_local = E / D;
+    for (int d = threadIdx.x; d < D; d += blockDim.x) {
+        int load = 0, vis = 0;
+        for (int e = 0; e < n_local; ++e) { load += tot[d * n_local + e]; vis += tot[E + d * n_local + e]; }
+        rank_load[d] = load;
+        rank_vis[d] = vis;
+        if (stats_host) {                             // pinned host copy for the policy: saves two copy launches
+            stats_host[d] = load;
+            stats_host[D + d] = vis;
+        }
+    }
+}
+
+}  // namespace realb

@@ -4,6 +4,7 @@
 // Stands in for the all-to-all dispatch of the paper's pipeline (Sec.
 // "Overhead-Aware Pipeline Orchestration"); the weight encoder overlaps it.
 #include "common.h"
+#include "hist_reduce.h"
 #include "mxfp4_device.h"
 
 namespace realb {
@@ -51,10 +52,10 @@ __device__ __forceinline__ int wave_inclusive_scan(int v, int /*lane*/) {
 // the exclusive scan over experts gives expert_offsets.  A wave takes an expert and walks its
 // column 64 chunks at a time; the loads of up to 16 such steps are issued together (one memory
 // latency instead of one per step), then the steps are scanned in order with a running carry.
-__global__ void __launch_bounds__(1024) perm_scan_kernel(int32_t* __restrict__ wave_cnt, int n_chunks, int n_local,
-                                                         int32_t* __restrict__ expert_offsets) {
+// totals: 64 ints of LDS.
+__device__ __forceinline__ void perm_scan_body(int* totals, int32_t* __restrict__ wave_cnt, int n_chunks, int n_local,
+                                               int32_t* __restrict__ expert_offsets) {
     constexpr int BATCH = 16;
-    __shared__ int totals[64];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int n_waves = blockDim.x >> 6;
@@ -83,6 +84,25 @@ __global__ void __launch_bounds__(1024) perm_scan_kernel(int32_t* __restrict__ w
         for (int e = 0; e < n_local; ++e) { expert_offsets[e] = run; run += totals[e]; }
         expert_offsets[n_local] = run;
     }
+}
+
+__global__ void __launch_bounds__(1024) perm_scan_kernel(int32_t* __restrict__ wave_cnt, int n_chunks, int n_local,
+                                                         int32_t* __restrict__ expert_offsets) {
+    __shared__ int totals[64];
+    perm_scan_body(totals, wave_cnt, n_chunks, n_local, expert_offsets);
+}
+
+// The layer call's two one-block jobs in one launch of two blocks, which run side by side: block 0 adds up the
+// routing kernel's partial histograms (and hands the per-rank statistics to the host), block 1 scans the
+// permutation's chunk counts.  One kernel boundary less on a path made of short, latency-bound kernels.
+__global__ void __launch_bounds__(1024) reduce_and_scan_kernel(const int32_t* __restrict__ hist_part, int n_part, int E, int D,
+                                                               int32_t* __restrict__ expert_cnt, int32_t* __restrict__ expert_vis,
+                                                               int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis,
+                                                               int32_t* __restrict__ stats_host, int32_t* __restrict__ wave_cnt,
+                                                               int n_chunks, int n_local, int32_t* __restrict__ expert_offsets) {
+    extern __shared__ int32_t dyn[];                  // max(2*E, 64) ints
+    if (blockIdx.x == 0) hist_reduce_body(dyn, hist_part, n_part, E, D, expert_cnt, expert_vis, rank_load, rank_vis, stats_host);
+    else perm_scan_body(dyn, wave_cnt, n_chunks, n_local, expert_offsets);
 }
 
 // Phase 3: each wave walks its chunk again and gives every local assignment its
@@ -225,6 +245,39 @@ int permute_indices(Ctx* c, const int32_t* topk_ids, int T, int rank, long long 
     if (n_chunks > 0)
         hipLaunchKernelGGL(perm_count_kernel, dim3(chunk_blocks), dim3(256), 0, s, topk_ids, (int)A, lo, n_local, n_chunks, c->wave_cnt);
     hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, s, c->wave_cnt, n_chunks, n_local, expert_offsets);
+    if (n_chunks > 0)
+        hipLaunchKernelGGL(perm_rank_kernel, dim3(chunk_blocks), dim3(256), 0, s, topk_ids, (int)A, lo, n_local, n_chunks,
+                           c->wave_cnt, expert_offsets, row_to_assign, assign_to_row);
+    REALB_HIP(hipGetLastError());
+    return REALB_OK;
+}
+
+// Routing and the permutation's index kernels as the layer call issues them: top-k + histograms, chunk counts,
+// [histogram reduce | chunk scan] in one launch, then -- behind the event that tells the host the statistics have
+// reached pinned memory -- the ranking kernel.
+int route_and_index(Ctx* c, const float* logits, const uint8_t* is_vision, int T, int rank, long long max_rows, int32_t* topk_ids,
+                    float* topk_w, int32_t* expert_cnt, int32_t* expert_vis, int32_t* rank_load, int32_t* rank_vis,
+                    int32_t* expert_offsets, int32_t* row_to_assign, int32_t* assign_to_row, hipEvent_t stats_ready, hipStream_t s) {
+    REALB_REQUIRE(c && expert_cnt && expert_vis && rank_load && rank_vis && expert_offsets, REALB_EINVAL, "NULL argument");
+    REALB_REQUIRE(T >= 0 && T <= c->cfg.T_max, REALB_ECAP, "T=%d outside [0, T_max=%d]", T, c->cfg.T_max);
+    REALB_REQUIRE(rank >= 0 && rank < c->cfg.D, REALB_EINVAL, "rank=%d outside [0,%d)", rank, c->cfg.D);
+    const int E = c->cfg.E, D = c->cfg.D, k = c->cfg.k, n_local = c->n_local;
+    const long long A = (long long)T * k;
+    const long long worst = (long long)T * (k < n_local ? k : n_local);
+    REALB_REQUIRE(max_rows >= worst, REALB_EINVAL, "max_rows=%lld is below the worst case %lld", max_rows, worst);
+    REALB_REQUIRE(T == 0 || (topk_ids && row_to_assign && assign_to_row), REALB_EINVAL, "NULL argument");
+    const int n_part = route_topk_only(c, logits, is_vision, T, topk_ids, topk_w, s);
+    if (n_part < 0) return n_part;
+    const int n_chunks = ceil_div(A, kPermChunk);
+    const int lo = rank * n_local;
+    const int chunk_blocks = ceil_div(n_chunks, 4);
+    if (n_chunks > 0)
+        hipLaunchKernelGGL(perm_count_kernel, dim3(chunk_blocks), dim3(256), 0, s, topk_ids, (int)A, lo, n_local, n_chunks, c->wave_cnt);
+    const size_t lds = (size_t)(2 * E > 64 ? 2 * E : 64) * sizeof(int32_t);
+    hipLaunchKernelGGL(reduce_and_scan_kernel, dim3(2), dim3(1024), lds, s, c->hist_part, n_part, E, D, expert_cnt, expert_vis,
+                       rank_load, rank_vis, c->stats_host, c->wave_cnt, n_chunks, n_local, expert_offsets);
+    REALB_HIP(hipGetLastError());
+    REALB_HIP(hipEventRecord(stats_ready, s));
     if (n_chunks > 0)
         hipLaunchKernelGGL(perm_rank_kernel, dim3(chunk_blocks), dim3(256), 0, s, topk_ids, (int)A, lo, n_local, n_chunks,
                            c->wave_cnt, expert_offsets, row_to_assign, assign_to_row);

@@ -3,6 +3,7 @@
 // with gates renormalised over the selected experts, per-expert and per-rank
 // assignment counts, split by modality.
 #include "common.h"
+#include "hist_reduce.h"
 #include <math.h>
 #include <mutex>
 
@@ -182,55 +183,18 @@ __global__ void __launch_bounds__(1024, 2) topk_hist_rows_kernel(const float* __
     for (int i = threadIdx.x; i < 2 * E; i += blockDim.x) hist_part[(size_t)blockIdx.x * 2 * E + i] = hist[i];
 }
 
-// Adds up the blocks' partial histograms and the per-rank sums (also written to the context's pinned
-// host buffer, which realb_layer_forward reads after one stream synchronisation) (a separate launch: the kernel
-// boundary makes the partials of all XCDs visible).  Thread layout: counter c = tid % CW,
-// slice = tid / CW; each slice walks its share of the partials, LDS atomics merge the slices.
 __global__ void __launch_bounds__(1024) hist_reduce_kernel(const int32_t* __restrict__ hist_part, int n_part, int E, int D,
                                                            int32_t* __restrict__ expert_cnt, int32_t* __restrict__ expert_vis,
                                                            int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis,
                                                            int32_t* __restrict__ stats_host) {
     extern __shared__ int32_t tot[];                  // [2*E]
-    const int C2 = 2 * E;
-    for (int i = threadIdx.x; i < C2; i += blockDim.x) tot[i] = 0;
-    __syncthreads();
-    int cw = 1;
-    while (cw < C2) cw <<= 1;                         // counters per slice row, power of two, <= 1024
-    const int n_slices = blockDim.x / cw;
-    const int c = threadIdx.x % cw, slice = threadIdx.x / cw;
-    if (c < C2 && slice < n_slices) {
-        int sum = 0;
-        int b = slice;
-        for (; b + 31 * n_slices < n_part; b += 32 * n_slices) {       // 32 independent loads in flight per thread
-            int v[32];
-#pragma unroll
-            for (int i = 0; i < 32; ++i) v[i] = hist_part[(size_t)(b + i * n_slices) * C2 + c];
-#pragma unroll
-            for (int i = 0; i < 32; ++i) sum += v[i];
-        }
-        for (; b < n_part; b += n_slices) sum += hist_part[(size_t)b * C2 + c];
-        if (sum) atomicAdd(&tot[c], sum);
-    }
-    __syncthreads();
-    for (int i = threadIdx.x; i < E; i += blockDim.x) { expert_cnt[i] = tot[i]; expert_vis[i] = tot[E + i]; }
-    const int n_local = E / D;
-    for (int d = threadIdx.x; d < D; d += blockDim.x) {
-        int load = 0, vis = 0;
-        for (int e = 0; e < n_local; ++e) { load += tot[d * n_local + e]; vis += tot[E + d * n_local + e]; }
-        rank_load[d] = load;
-        rank_vis[d] = vis;
-        if (stats_host) {                             // pinned host copy for the policy: saves two copy launches
-            stats_host[d] = load;
-            stats_host[D + d] = vis;
-        }
-    }
+    hist_reduce_body(tot, hist_part, n_part, E, D, expert_cnt, expert_vis, rank_load, rank_vis, stats_host);
 }
 
-// Launches the top-k + histogram kernel and the reduce.  hist_part must hold max_blocks * 2E counters;
-// stats_host (pinned host memory) may be NULL.
-static int launch_route_stats(int num_cus, int max_blocks, int32_t* hist_part, int32_t* stats_host, const float* logits,
-                              const uint8_t* is_vision, int T, int E, int k, int D, int32_t* topk_ids, float* topk_w,
-                              int32_t* expert_cnt, int32_t* expert_vis, int32_t* rank_load, int32_t* rank_vis, hipStream_t s) {
+// Launches the top-k + histogram kernel; returns the number of blocks (= partial histograms written).
+// hist_part must hold max_blocks * 2E counters.
+static int launch_topk(int num_cus, int max_blocks, int32_t* hist_part, const float* logits, const uint8_t* is_vision, int T,
+                       int E, int k, int32_t* topk_ids, float* topk_w, hipStream_t s) {
     int blocks = 0;
     if (T > 0) {
         const size_t lds = 2 * (size_t)E * sizeof(int32_t);
@@ -263,10 +227,28 @@ static int launch_route_stats(int num_cus, int max_blocks, int32_t* hist_part, i
 #undef REALB_TOPK
         }
     }
+    return blocks;
+}
+
+// The top-k + histogram kernel and the reduce.  stats_host (pinned host memory) may be NULL.
+static int launch_route_stats(int num_cus, int max_blocks, int32_t* hist_part, int32_t* stats_host, const float* logits,
+                              const uint8_t* is_vision, int T, int E, int k, int D, int32_t* topk_ids, float* topk_w,
+                              int32_t* expert_cnt, int32_t* expert_vis, int32_t* rank_load, int32_t* rank_vis, hipStream_t s) {
+    const int blocks = launch_topk(num_cus, max_blocks, hist_part, logits, is_vision, T, E, k, topk_ids, topk_w, s);
     hipLaunchKernelGGL(hist_reduce_kernel, dim3(1), dim3(1024), 2 * (size_t)E * sizeof(int32_t), s, hist_part, blocks, E, D,
                        expert_cnt, expert_vis, rank_load, rank_vis, stats_host);
     REALB_HIP(hipGetLastError());
     return REALB_OK;
+}
+
+// Routing for the layer call: only the top-k + histogram kernel; the reduce is fused with the permutation's scan
+// (route_and_index in permute.hip).  Returns the number of partial histograms, or a negative error code.
+int route_topk_only(Ctx* c, const float* logits, const uint8_t* is_vision, int T, int32_t* topk_ids, float* topk_w, hipStream_t s) {
+    REALB_REQUIRE(T >= 0 && T <= c->cfg.T_max, REALB_ECAP, "T=%d outside [0, T_max=%d]", T, c->cfg.T_max);
+    REALB_REQUIRE(T == 0 || (logits && is_vision && topk_ids && topk_w), REALB_EINVAL, "NULL argument");
+    const int blocks = launch_topk(c->num_cus, kRouteBlocksMax, c->hist_part, logits, is_vision, T, c->cfg.E, c->cfg.k, topk_ids, topk_w, s);
+    REALB_HIP(hipGetLastError());
+    return blocks;
 }
 
 // ---- the allocation-free variant's scratch: the per-block partial histograms, in a file-scope device array.
