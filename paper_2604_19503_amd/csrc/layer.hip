@@ -85,7 +85,10 @@ static int rank_forward_steps(realb_ctx* ctx, realb_layer_io* io, int prec, void
         if (rc != REALB_OK) return rc;
     }
     stage_mark(c, s, 4);
-    if (fp4 && ((side && !encoded) || act_in_flight)) REALB_HIP(hipStreamWaitEvent(s, c->ev_join, 0));
+    // speculative weights: the gate/up GEMM needs the activations and W13 only (ev_gate); W2's encoding may still run beside it
+    const bool split_join = fp4 && quant_in_flight && gather;
+    if (split_join) REALB_HIP(hipStreamWaitEvent(s, c->ev_gate, 0));
+    else if (fp4 && ((side && !encoded) || act_in_flight)) REALB_HIP(hipStreamWaitEvent(s, c->ev_join, 0));
     if (prefetch) {
         REALB_HIP(hipEventRecord(c->ev_fork, s));         // the prefetch may start once the stream is here, beside the GEMMs
         c->gemm_reserve = io->reserve_cus;
@@ -106,6 +109,7 @@ static int rank_forward_steps(realb_ctx* ctx, realb_layer_io* io, int prec, void
         stage_mark(c, s, 5);
         rc = issue_prefetch();
         if (rc != REALB_OK) return rc;
+        if (split_join) REALB_HIP(hipStreamWaitEvent(s, c->ev_join, 0));
         rc = realb_grouped_moe_ffn_down(ctx, prec, io->expert_offsets, c->n_local, io->max_rows, io->h_mid, fp4 ? io->h_s : nullptr,
                                         fp4 ? (const void*)io->w2_q : io->w2, fp4 ? io->w2_s : nullptr, io->y_rows, stream);
     } else if (fp4) {
@@ -180,9 +184,15 @@ extern "C" int realb_layer_forward(realb_ctx* ctx, realb_layer_io* io, void* str
         REALB_HIP(hipEventRecord(c->ev_fork, s));
         REALB_HIP(hipStreamWaitEvent(c->side, c->ev_fork, 0));
         rc = REALB_OK;
+        // side stream, in the order the GEMMs need them: activations, W13 (-> ev_gate), W2 (-> ev_join)
         if (spec_x) rc = launch_quantize_flat(io->x, io->T, c->cfg.H, io->x_q, io->x_s, nullptr, 0, 0, nullptr, nullptr, c->side);
         if (rc == REALB_OK && spec_w)
-            rc = realb_quantize_experts_fp4(ctx, io->w13, io->w2, c->n_local, io->w13_q, io->w13_s, io->w2_q, io->w2_s, c->side);
+            rc = launch_quantize_flat(io->w13, (long long)c->n_local * 2 * c->cfg.I, c->cfg.H, io->w13_q, io->w13_s, nullptr, 0, 0, nullptr,
+                                      nullptr, c->side);
+        REALB_HIP(hipEventRecord(c->ev_gate, c->side));
+        if (rc == REALB_OK && spec_w)
+            rc = launch_quantize_flat(io->w2, (long long)c->n_local * c->cfg.H, c->cfg.I, io->w2_q, io->w2_s, nullptr, 0, 0, nullptr, nullptr,
+                                      c->side);
         REALB_HIP(hipEventRecord(c->ev_join, c->side));
         if (rc != REALB_OK) { (void)hipStreamWaitEvent(s, c->ev_join, 0); return rc; }
     }
