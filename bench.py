@@ -159,6 +159,8 @@ def parse():
                          "stream after the decision; side = side stream after the decision (under the permutation).  The step is timed "
                          "in all of them, in rotated order, and reported under extra")
     ap.add_argument("--reserve-cus", type=int, default=0, help="compute units the GEMMs leave to the encoder in prefetch mode")
+    ap.add_argument("--only-headline", action="store_true",
+                    help="time the headline placement only (profiling runs: every launch of a kernel then belongs to the same placement)")
     ap.add_argument("--no-compare", action="store_true", help="skip the brief BF16 pass and the c3 pair folded into the default line")
     ap.add_argument("--gemm-tile", type=int, default=0, choices=[0, 2, 8, 16], help="grouped-GEMM block tile selector (0 = automatic)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -653,7 +655,7 @@ def main():
     # ---- timed region: exactly K steps of the headline placement.  The other placements of the weight encoding are
     #      timed beside it in rotated order (K steps each as well, in `rounds` chunks), so that no placement always
     #      runs first or last.
-    modes = [mode] + [m for m in ENCODE_MODES if m != mode] if fp4 else [mode]
+    modes = [mode] + [m for m in ENCODE_MODES if m != mode] if (fp4 and not args.only_headline) else [mode]
     steppers = {m: (step if m == mode else lr.stepper(fp4, m)) for m in modes}
     rounds = max(1, min(4, args.steps))
     chunk = [args.steps // rounds + (1 if r < args.steps % rounds else 0) for r in range(rounds)]

@@ -287,7 +287,7 @@ int realb_rank_forward(realb_ctx* ctx, realb_layer_io* io, int prec, void* strea
  * the last call and returns, in milliseconds, how long each stage of THAT call took on the GPU:
  *   [0] route_stats  [1] permutation indices (realb_layer_forward interleaves the two groups of kernels and reports
  *   their sum under [0])  [2] host decision + weight encoding on the caller's stream
- *   [3] gather / activation encoding  [4] gate/up GEMM  [5] down GEMM  [6] combine
+ *   [3] gather / activation encoding, incl. any wait for the side stream's encoders  [4] gate/up GEMM  [5] down GEMM  [6] combine
  * (realb_rank_forward: [0] is 0).  ms_host receives REALB_N_STAGES floats.  REALB_EINVAL if timing is
  * off or no call has been made since it was switched on. */
 enum { REALB_N_STAGES = 7 };

@@ -84,7 +84,6 @@ static int rank_forward_steps(realb_ctx* ctx, realb_layer_io* io, int prec, void
         rc = permute_gather(c, io->x, io->assign_to_row, io->T, prec, io->x_perm, io->x_q, io->x_s, s, gather ? 1 : 0);
         if (rc != REALB_OK) return rc;
     }
-    stage_mark(c, s, 4);
     // speculative weights: the gate/up GEMM needs the activations and W13 only (ev_gate); W2's encoding may still run beside it
     const bool split_join = fp4 && quant_in_flight && gather;
     if (split_join) REALB_HIP(hipStreamWaitEvent(s, c->ev_gate, 0));
@@ -94,6 +93,7 @@ static int rank_forward_steps(realb_ctx* ctx, realb_layer_io* io, int prec, void
         c->gemm_reserve = io->reserve_cus;
     }
     struct ReserveReset { Ctx* c; ~ReserveReset() { c->gemm_reserve = 0; } } reserve_reset{c};
+    stage_mark(c, s, 4);                              // (behind the joins: waiting for the side stream counts as stage [3])
     if (gather) {
         REALB_REQUIRE(io->h_mid && io->w2 && io->y_rows, REALB_EINVAL, "NULL argument");
         if (fp4) {
@@ -201,8 +201,8 @@ extern "C" int realb_layer_forward(realb_ctx* ctx, realb_layer_io* io, void* str
     stage_mark(c, as_stream(stream), 0);
     // The statistics reach pinned host memory with the histogram reduce.  The permutation's index kernels do not
     // depend on the precision, so they are interleaved with the routing kernels (the reduce shares a launch with
-    // the permutation's scan) and the last of them runs while the host waits for the event, takes the decision
-    // and launches the rest: the GPU does not idle across the decision.
+    // the permutation's count kernel) and the last two of them run while the host waits for the event, takes the
+    // decision and launches the rest.
     rc = route_and_index(c, io->logits, io->is_vision, io->T, io->rank, io->max_rows, io->topk_ids, io->topk_w, io->expert_cnt,
                          io->expert_vis, io->rank_load, io->rank_vis, io->expert_offsets, io->row_to_assign, io->assign_to_row,
                          c->ev_stats, as_stream(stream));

@@ -13,10 +13,9 @@ constexpr int kIters = kPermChunk / 64;   // 64 assignments per wave iteration
 
 // Phase 1: each wave counts, per local expert, the assignments of its chunk of
 // kPermChunk consecutive flat indices a = t*k + j.  Lane e holds expert e's count.
-__global__ void __launch_bounds__(256) perm_count_kernel(const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
-                                                         int n_chunks, int32_t* __restrict__ wave_cnt) {
+__device__ __forceinline__ void perm_count_body(int chunk, const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
+                                                int n_chunks, int32_t* __restrict__ wave_cnt) {
     const int lane = threadIdx.x & 63;
-    const int chunk = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (chunk >= n_chunks) return;
     const int begin = chunk * kPermChunk;
     int le[kIters];
@@ -33,6 +32,11 @@ __global__ void __launch_bounds__(256) perm_count_kernel(const int32_t* __restri
             if (lane == e) cnt += __popcll(m);
         }
     if (lane < n_local) wave_cnt[(size_t)lane * n_chunks + chunk] = cnt;     // expert-major: the scan reads a column contiguously
+}
+
+__global__ void __launch_bounds__(256) perm_count_kernel(const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
+                                                         int n_chunks, int32_t* __restrict__ wave_cnt) {
+    perm_count_body(blockIdx.x * 4 + (threadIdx.x >> 6), topk_ids, A, lo, n_local, n_chunks, wave_cnt);
 }
 
 // Inclusive prefix sum over the 64 lanes with DPP only: four shifts inside each row of 16 lanes, then the
@@ -92,17 +96,18 @@ __global__ void __launch_bounds__(1024) perm_scan_kernel(int32_t* __restrict__ w
     perm_scan_body(totals, wave_cnt, n_chunks, n_local, expert_offsets);
 }
 
-// The layer call's two one-block jobs in one launch of two blocks, which run side by side: block 0 adds up the
-// routing kernel's partial histograms (and hands the per-rank statistics to the host), block 1 scans the
-// permutation's chunk counts.  One kernel boundary less on a path made of short, latency-bound kernels.
-__global__ void __launch_bounds__(1024) reduce_and_scan_kernel(const int32_t* __restrict__ hist_part, int n_part, int E, int D,
-                                                               int32_t* __restrict__ expert_cnt, int32_t* __restrict__ expert_vis,
-                                                               int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis,
-                                                               int32_t* __restrict__ stats_host, int32_t* __restrict__ wave_cnt,
-                                                               int n_chunks, int n_local, int32_t* __restrict__ expert_offsets) {
-    extern __shared__ int32_t dyn[];                  // max(2*E, 64) ints
+// The layer call's histogram reduce shares a launch with the permutation's count kernel: block 0 adds up the routing
+// kernel's partial histograms (and hands the per-rank statistics to the host), the other blocks count their chunks,
+// 16 per block.  One kernel boundary less on a path made of short, latency-bound kernels, and the host learns the
+// statistics two kernels (scan, rank) before the stream runs dry.
+__global__ void __launch_bounds__(1024) reduce_and_count_kernel(const int32_t* __restrict__ hist_part, int n_part, int E, int D,
+                                                                int32_t* __restrict__ expert_cnt, int32_t* __restrict__ expert_vis,
+                                                                int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis,
+                                                                int32_t* __restrict__ stats_host, const int32_t* __restrict__ topk_ids,
+                                                                int A, int lo, int n_local, int n_chunks, int32_t* __restrict__ wave_cnt) {
+    extern __shared__ int32_t dyn[];                  // 2*E ints (block 0 only)
     if (blockIdx.x == 0) hist_reduce_body(dyn, hist_part, n_part, E, D, expert_cnt, expert_vis, rank_load, rank_vis, stats_host);
-    else perm_scan_body(dyn, wave_cnt, n_chunks, n_local, expert_offsets);
+    else perm_count_body((blockIdx.x - 1) * 16 + (threadIdx.x >> 6), topk_ids, A, lo, n_local, n_chunks, wave_cnt);
 }
 
 // Phase 3: each wave walks its chunk again and gives every local assignment its
@@ -252,9 +257,9 @@ int permute_indices(Ctx* c, const int32_t* topk_ids, int T, int rank, long long 
     return REALB_OK;
 }
 
-// Routing and the permutation's index kernels as the layer call issues them: top-k + histograms, chunk counts,
-// [histogram reduce | chunk scan] in one launch, then -- behind the event that tells the host the statistics have
-// reached pinned memory -- the ranking kernel.
+// Routing and the permutation's index kernels as the layer call issues them: top-k + histograms, then
+// [histogram reduce | chunk counts] in one launch, then -- behind the event that tells the host the statistics have
+// reached pinned memory -- the scan and the ranking kernel, which run while the host takes the decision.
 int route_and_index(Ctx* c, const float* logits, const uint8_t* is_vision, int T, int rank, long long max_rows, int32_t* topk_ids,
                     float* topk_w, int32_t* expert_cnt, int32_t* expert_vis, int32_t* rank_load, int32_t* rank_vis,
                     int32_t* expert_offsets, int32_t* row_to_assign, int32_t* assign_to_row, hipEvent_t stats_ready, hipStream_t s) {
@@ -271,13 +276,12 @@ int route_and_index(Ctx* c, const float* logits, const uint8_t* is_vision, int T
     const int n_chunks = ceil_div(A, kPermChunk);
     const int lo = rank * n_local;
     const int chunk_blocks = ceil_div(n_chunks, 4);
-    if (n_chunks > 0)
-        hipLaunchKernelGGL(perm_count_kernel, dim3(chunk_blocks), dim3(256), 0, s, topk_ids, (int)A, lo, n_local, n_chunks, c->wave_cnt);
-    const size_t lds = (size_t)(2 * E > 64 ? 2 * E : 64) * sizeof(int32_t);
-    hipLaunchKernelGGL(reduce_and_scan_kernel, dim3(2), dim3(1024), lds, s, c->hist_part, n_part, E, D, expert_cnt, expert_vis,
-                       rank_load, rank_vis, c->stats_host, c->wave_cnt, n_chunks, n_local, expert_offsets);
+    hipLaunchKernelGGL(reduce_and_count_kernel, dim3(1 + ceil_div(n_chunks, 16)), dim3(1024), 2 * (size_t)E * sizeof(int32_t), s,
+                       c->hist_part, n_part, E, D, expert_cnt, expert_vis, rank_load, rank_vis, c->stats_host, topk_ids, (int)A, lo,
+                       n_local, n_chunks, c->wave_cnt);
     REALB_HIP(hipGetLastError());
     REALB_HIP(hipEventRecord(stats_ready, s));
+    hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, s, c->wave_cnt, n_chunks, n_local, expert_offsets);
     if (n_chunks > 0)
         hipLaunchKernelGGL(perm_rank_kernel, dim3(chunk_blocks), dim3(256), 0, s, topk_ids, (int)A, lo, n_local, n_chunks,
                            c->wave_cnt, expert_offsets, row_to_assign, assign_to_row);
