@@ -152,10 +152,10 @@ def parse():
     ap.add_argument("--iterations", type=int, default=100, help="trace length of the policy ablation")
     ap.add_argument("--precision", default="fp4", choices=["fp4", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--encode-mode", default="prefetch", choices=list(ENCODE_MODES),
-                    help="where the FP4 weight encoding runs: prefetch (default) = layer pipeline, each step encodes the next layer's weights "
-                         "on the side stream beside its own GEMMs; speculative = side stream before routing, beside the routing and index "
-                         "kernels; main = caller's "
+    ap.add_argument("--encode-mode", default="speculative", choices=list(ENCODE_MODES),
+                    help="where the FP4 weight encoding runs: speculative (default) = side stream ahead of the decision, beside the routing and "
+                         "index kernels; prefetch = layer pipeline, each step encodes the next layer's weights on the side stream beside "
+                         "its own GEMMs; main = caller's "
                          "stream after the decision; side = side stream after the decision (under the permutation).  The step is timed "
                          "in all of them, in rotated order, and reported under extra")
     ap.add_argument("--reserve-cus", type=int, default=0, help="compute units the GEMMs leave to the encoder in prefetch mode")

@@ -187,3 +187,53 @@ def test_config5_three_weight_sets_and_pre_encoded_call():
     assert torch.equal(buf.w13_q, ref_wq)
     _say("c5: pre-encoded call reproduces the rows bit for bit")
     ctx.close()
+
+
+def test_policy_variants_choose_the_oracles_fp4_sets():
+    """The four policy variants of the threshold study (AIMD with either update order, the fixed thresholds M = 0 and
+    M = 0.7) on two seeded iterations of the simulated trace -- a clustered and a scattered one -- with the routing
+    statistics taken from the GPU and the state carried from the first iteration to the second: the FP4 sets, IB_global
+    and M must be the oracle's, through the context call and through the host function."""
+    import paper_2604_19503_amd as R
+    from paper_2604_19503_amd.binding import default_config, select_precision_host
+    cfg = W.CONFIGS["c4"]
+    _, isv_np = W.gen_tokens(cfg, 0)
+    isv = torch.from_numpy(isv_np).cuda()
+    variants = {"aimd_update_first": dict(aimd_enabled=1, M_init=0.9, update_first=1),
+                "aimd_decide_first": dict(aimd_enabled=1, M_init=0.9, update_first=0),
+                "fixed_m1": dict(aimd_enabled=0, M_init=0.0, update_first=1),
+                "fixed_m2": dict(aimd_enabled=0, M_init=0.7, update_first=1)}
+    iterations = (10, 20)                                    # clustered block, scattered block of the trace generator
+    stats = []
+    rcfg0 = default_config(cfg.T, cfg.E, cfg.k, cfg.D, cfg.H, cfg.I)
+    ctx0 = R.Context(rcfg0)
+    buf = R.LayerBuffers(rcfg0, cfg.T)
+    for it in iterations:
+        logits, info = W.gen_logits_trace(cfg, it, isv_np)
+        ctx0.route_stats(torch.from_numpy(logits).cuda(), isv, buf)
+        torch.cuda.synchronize()
+        ids, _ = orouter.topk_route(logits, cfg.k)
+        _, _, load, rvis = orouter.route_counts(ids, isv_np, cfg.E, cfg.D)
+        assert same(buf.rank_load.cpu().numpy(), load) and same(buf.rank_vis.cpu().numpy(), rvis)
+        stats.append((buf.rank_load.clone(), buf.rank_vis.clone(), load, rvis, info["kind"]))
+    ctx0.close()
+    assert {s[4] for s in stats} == {"clustered", "scattered"}
+    fired = 0
+    for name, kw in variants.items():
+        rcfg = default_config(cfg.T, cfg.E, cfg.k, cfg.D, cfg.H, cfg.I)
+        rcfg.aimd_enabled, rcfg.M_init, rcfg.update_first = kw["aimd_enabled"], kw["M_init"], kw["update_first"]
+        ctx = R.Context(rcfg)
+        pc = opol.PolicyConfig(aimd_enabled=bool(kw["aimd_enabled"]), M_init=kw["M_init"], update_first=bool(kw["update_first"]))
+        M_or = M_host = kw["M_init"]
+        for load_d, vis_d, load, rvis, kind in stats:
+            buf.rank_load.copy_(load_d); buf.rank_vis.copy_(vis_d)
+            prec, ib, M_ctx = ctx.select_precision(buf, cfg.T)
+            want = opol.select_precision(load, rvis, cfg.T, cfg.k, M_or, pc)
+            M_or = want[2]
+            ph, ibh, M_host = select_precision_host(rcfg, load, rvis, cfg.T, M_host)
+            _say(f"policy {name} on a {kind} iteration: FP4 ranks {list(np.nonzero(prec)[0])}, IB_global {ib:.3f}, M {M_ctx}")
+            assert list(prec) == list(want[0]) == list(ph)
+            assert ib == want[1] == ibh and M_ctx == want[2] == M_host == ctx.M
+            fired += int(np.sum(prec))
+        ctx.close()
+    assert fired > 0                                         # the cases are not vacuous: some variant converts some rank
