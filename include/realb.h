@@ -288,8 +288,8 @@ int realb_rank_forward(realb_ctx* ctx, realb_layer_io* io, int prec, void* strea
  *   [0] route_stats  [1] permutation indices (realb_layer_forward interleaves the two groups of kernels and reports
  *   their sum under [0])  [2] host decision + weight encoding on the caller's stream
  *   [3] gather / activation encoding, incl. any wait for the side stream's encoders  [4] gate/up GEMM  [5] down GEMM  [6] combine
- * (realb_rank_forward: [0] is 0).  ms_host receives REALB_N_STAGES floats.  REALB_EINVAL if timing is
- * off or no call has been made since it was switched on. */
+ * (realb_rank_forward: [0] holds only the few microseconds between two markers).  ms_host receives
+ * REALB_N_STAGES floats.  REALB_EINVAL if timing is off or no call has been made since it was switched on. */
 enum { REALB_N_STAGES = 7 };
 int realb_stage_timing(realb_ctx* ctx, int enable);
 int realb_stage_ms(realb_ctx* ctx, float* ms_host);

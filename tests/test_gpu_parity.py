@@ -465,6 +465,36 @@ def test_cross_layer_prefetch_pipeline_is_bit_identical(R, reserve):
     ctx.close()
 
 
+def test_stage_timing_reports_the_stages_of_the_last_call(R, case):
+    """realb_stage_timing / realb_stage_ms: seven non-negative stage times whose sum is of the order of the call's
+    wall time, in both call forms; an error while timing is off; outputs unchanged by the timing events."""
+    import time
+    b = case.buf
+    io = case.ctx.make_io(case.logits, case.is_vision, case.x, case.w13, case.w2, b, case.rank, force=R.FP4, overlap=0)
+    case.ctx.layer_forward(io)
+    _sync()
+    ref = b.out.clone()
+    with pytest.raises(R.RealbError):
+        case.ctx.stage_ms()
+    case.ctx.stage_timing(True)
+    with pytest.raises(R.RealbError):
+        case.ctx.stage_ms()                                   # no layer call yet since it was switched on
+    t0 = time.perf_counter()
+    case.ctx.layer_forward(io)
+    ms = case.ctx.stage_ms()
+    wall = (time.perf_counter() - t0) * 1e3
+    assert list(ms) == list(case.ctx.STAGES) and all(v >= 0 for v in ms.values())
+    assert 0 < ms["gate_up"] and 0 < ms["down"] and 0 < ms["combine"] and sum(ms.values()) <= wall * 1.05
+    assert torch.equal(b.out.view(torch.int16), ref.view(torch.int16))
+    case.ctx.rank_forward(io, R.BF16)
+    ms2 = case.ctx.stage_ms()
+    assert ms2["route_stats"] < 0.02 and ms2["gate_up"] > 0            # two markers back to back: a few microseconds
+    case.ctx.stage_timing(False)
+    with pytest.raises(R.RealbError):
+        case.ctx.stage_ms()
+    _sync()
+
+
 # ---------------------------------------------------------------------------- edge cases
 def test_edge_empty_batch_and_empty_rank_and_empty_expert(R):
     from paper_2604_19503_amd.binding import default_config
