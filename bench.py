@@ -657,7 +657,7 @@ def main():
     #      runs first or last.
     modes = [mode] + [m for m in ENCODE_MODES if m != mode] if (fp4 and not args.only_headline) else [mode]
     steppers = {m: (step if m == mode else lr.stepper(fp4, m)) for m in modes}
-    rounds = max(1, min(4, args.steps))
+    rounds = max(1, min(4, args.steps // 10))             # chunks of at least 10 steps: a chunk's first step starts on an idle GPU
     chunk = [args.steps // rounds + (1 if r < args.steps % rounds else 0) for r in range(rounds)]
     total = {m: 0.0 for m in modes}
     for r in range(rounds):
