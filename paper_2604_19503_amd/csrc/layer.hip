@@ -1,11 +1,33 @@
 // The rank layer end to end: the paper's four-stage pipeline (Sec. "System
-// Overview") with the weight transformation overlapped with dispatch packing
-// (Sec. "Overhead-Aware Pipeline Orchestration"): the encoder runs on the
-// context's side stream while the permutation runs on the caller's stream, and
-// is joined before the GEMMs.
+// Overview") with the weight transformation overlapped with other work
+// (Sec. "Overhead-Aware Pipeline Orchestration"): the encoders run on the
+// context's side stream -- after the decision beside the permutation, ahead of
+// the decision beside the routing and index kernels, or, for the NEXT layer's
+// weights, beside this layer's GEMMs -- and are joined before the kernels that
+// read their output.
 #include "common.h"
 
 using namespace realb;
+
+// Checks of a layer call's arguments that do not depend on the precision; made before anything is enqueued.
+static int validate_io(const Ctx* c, const realb_layer_io* io) {
+    REALB_REQUIRE(io->T >= 0 && io->T <= c->cfg.T_max, REALB_ECAP, "T=%d outside [0, T_max=%d]", io->T, c->cfg.T_max);
+    REALB_REQUIRE(io->rank >= 0 && io->rank < c->cfg.D, REALB_EINVAL, "rank=%d outside [0,%d)", io->rank, c->cfg.D);
+    REALB_REQUIRE(io->max_rows >= (long long)io->T * (c->cfg.k < c->n_local ? c->cfg.k : c->n_local), REALB_EINVAL,
+                  "max_rows=%lld is below the worst case", io->max_rows);
+    REALB_REQUIRE(io->overlap >= 0 && io->overlap <= 4, REALB_EINVAL, "bad overlap value %d", io->overlap);
+    REALB_REQUIRE(io->expert_offsets && io->h_mid && io->y_rows && io->w2 && io->w13, REALB_EINVAL, "NULL argument");
+    REALB_REQUIRE(io->T == 0 || (io->x && io->topk_ids && io->topk_w && io->row_to_assign && io->assign_to_row && io->out), REALB_EINVAL,
+                  "NULL argument");
+    if (io->next_w13 != nullptr || io->next_w2 != nullptr) {      // cross-layer prefetch requested
+        REALB_REQUIRE(io->next_w13 && io->next_w2 && io->next_w13_q && io->next_w13_s && io->next_w2_q && io->next_w2_s, REALB_EINVAL,
+                      "cross-layer prefetch needs next_w13, next_w2 and all four next_* buffers");
+        REALB_REQUIRE(io->next_w13_q != io->w13_q && io->next_w13_s != io->w13_s && io->next_w2_q != io->w2_q && io->next_w2_s != io->w2_s,
+                      REALB_EINVAL, "the prefetch buffers must differ from this layer's FP4 weight buffers");
+        REALB_REQUIRE(io->reserve_cus >= 0 && io->reserve_cus < c->num_cus, REALB_EINVAL, "reserve_cus=%d outside [0, %d)", io->reserve_cus, c->num_cus);
+    }
+    return REALB_OK;
+}
 
 // quant_in_flight: the weight encoding was already issued on the side stream (speculative mode);
 // act_in_flight: so was the FP4 encoding of every token's activations (one row per token, the form the
@@ -21,24 +43,10 @@ static int rank_forward_steps(realb_ctx* ctx, realb_layer_io* io, int prec, void
     const bool fp4 = prec == REALB_FP4;
     const bool side = io->overlap == 1 || quant_in_flight;
     // everything that can be refused is checked before any work goes to the side stream
-    REALB_REQUIRE(io->T >= 0 && io->T <= c->cfg.T_max, REALB_ECAP, "T=%d outside [0, T_max=%d]", io->T, c->cfg.T_max);
-    REALB_REQUIRE(io->rank >= 0 && io->rank < c->cfg.D, REALB_EINVAL, "rank=%d outside [0,%d)", io->rank, c->cfg.D);
-    REALB_REQUIRE(io->max_rows >= (long long)io->T * (c->cfg.k < c->n_local ? c->cfg.k : c->n_local), REALB_EINVAL,
-                  "max_rows=%lld is below the worst case", io->max_rows);
-    REALB_REQUIRE(io->expert_offsets && io->h_mid && io->y_rows && io->w2 && io->w13, REALB_EINVAL, "NULL argument");
-    REALB_REQUIRE(io->T == 0 || (io->x && io->topk_ids && io->topk_w && io->row_to_assign && io->assign_to_row && io->out), REALB_EINVAL,
-                  "NULL argument");
+    rc = validate_io(c, io);
+    if (rc != REALB_OK) return rc;
     if (fp4) REALB_REQUIRE(io->w13_q && io->w13_s && io->w2_q && io->w2_s && io->x_q && io->x_s && io->h_s, REALB_EINVAL, "NULL FP4 buffer");
-    REALB_REQUIRE(io->overlap >= 0 && io->overlap <= 4, REALB_EINVAL, "bad overlap value %d", io->overlap);
-    // cross-layer prefetch of the NEXT layer's weights, beside this layer's GEMMs
-    const bool prefetch = io->next_w13 != nullptr || io->next_w2 != nullptr;
-    if (prefetch) {
-        REALB_REQUIRE(io->next_w13 && io->next_w2 && io->next_w13_q && io->next_w13_s && io->next_w2_q && io->next_w2_s, REALB_EINVAL,
-                      "cross-layer prefetch needs next_w13, next_w2 and all four next_* buffers");
-        REALB_REQUIRE(io->next_w13_q != io->w13_q && io->next_w13_s != io->w13_s && io->next_w2_q != io->w2_q && io->next_w2_s != io->w2_s,
-                      REALB_EINVAL, "the prefetch buffers must differ from this layer's FP4 weight buffers");
-        REALB_REQUIRE(io->reserve_cus >= 0 && io->reserve_cus < c->num_cus, REALB_EINVAL, "reserve_cus=%d outside [0, %d)", io->reserve_cus, c->num_cus);
-    }
+    const bool prefetch = io->next_w13 != nullptr;       // cross-layer prefetch of the NEXT layer's weights, beside this layer's GEMMs
     // weights encoded by the previous call's prefetch: everything this call enqueues from here on comes after it
     if (c->prefetch_pending && (io->overlap == 4 || prefetch)) {
         REALB_HIP(hipStreamWaitEvent(s, c->ev_prefetch, 0));
@@ -157,17 +165,15 @@ extern "C" int realb_rank_forward(realb_ctx* ctx, realb_layer_io* io, int prec, 
 extern "C" int realb_layer_forward(realb_ctx* ctx, realb_layer_io* io, void* stream) {
     REALB_REQUIRE(ctx && io, REALB_EINVAL, "NULL argument");
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
-    REALB_REQUIRE(io->rank >= 0 && io->rank < c->cfg.D, REALB_EINVAL, "rank=%d outside [0,%d)", io->rank, c->cfg.D);
-    int rc;
     // Everything that can be refused is checked before anything is enqueued.
+    int rc = validate_io(c, io);
+    if (rc != REALB_OK) return rc;
     REALB_REQUIRE(io->force == REALB_FORCE_NONE || io->force == REALB_BF16 || io->force == REALB_FP4, REALB_EINVAL,
                   "bad force value %d", io->force);
-    REALB_REQUIRE(io->T >= 0 && io->T <= c->cfg.T_max, REALB_ECAP, "T=%d outside [0, T_max=%d]", io->T, c->cfg.T_max);
-    REALB_REQUIRE(io->max_rows >= (long long)io->T * (c->cfg.k < c->n_local ? c->cfg.k : c->n_local), REALB_EINVAL,
-                  "max_rows=%lld is below the worst case", io->max_rows);
-    REALB_REQUIRE(io->expert_cnt && io->expert_vis && io->rank_load && io->rank_vis && io->expert_offsets, REALB_EINVAL, "NULL argument");
-    REALB_REQUIRE(io->T == 0 || (io->logits && io->is_vision && io->topk_ids && io->topk_w && io->row_to_assign && io->assign_to_row),
-                  REALB_EINVAL, "NULL argument");
+    REALB_REQUIRE(io->expert_cnt && io->expert_vis && io->rank_load && io->rank_vis, REALB_EINVAL, "NULL argument");
+    REALB_REQUIRE(io->T == 0 || (io->logits && io->is_vision), REALB_EINVAL, "NULL argument");
+    if (io->force == REALB_FP4)
+        REALB_REQUIRE(io->w13_q && io->w13_s && io->w2_q && io->w2_s && io->x_q && io->x_s && io->h_s, REALB_EINVAL, "NULL FP4 buffer");
     // Speculative mode: the weight encoding depends on the weights only, so it can start on the
     // side stream before routing and fill the window in which the GPU waits for the host's
     // precision decision.  If the decision is BF16 its output is simply not used.
