@@ -221,70 +221,71 @@ __device__ __forceinline__ void store_tile_pair(uint8_t* base, size_t row_pitch,
     store16<NT>(dst + row_pitch + 64, qb, row_a + 1 < rows_left);
 }
 
-// Epilogue, straight from registers.  acc[mt][t][r] belongs to activation row wm*128 + mt*32 + li
-// of the tile and to column 16*half + r of the wave's t-th 32-column tile.  rows_valid = rows of
-// this tile that exist (may exceed the tile height).
+// Epilogue of one 32-row tile of a wave (row tile `mt` of its four), straight from registers.  a[t][r] belongs to
+// activation row wm*128 + mt*32 + li of the block tile and to column 16*half + r of the wave's t-th 32-column tile.
+// rows_valid = rows of the block tile that exist (may exceed the tile height).
 template <bool FP4, bool GATEUP, int WN, bool NT>
-__device__ __forceinline__ void epilogue(const GemmParams& p, v16f_t (&acc)[4][WN], int row0, int rows_valid, int n0,
-                                         int wm, int wn, int li, int half) {
+__device__ __forceinline__ void epilogue_mt(const GemmParams& p, v16f_t (&a)[WN], int mt, int row0, int rows_valid, int n0,
+                                            int wm, int wn, int li, int half) {
     const int lane = half * 32 + li;
+    const int tile_row0 = wm * 128 + mt * 32;
     if constexpr (GATEUP) {
         constexpr int HT = WN / 2;                     // h column tiles per wave
+        const int m = tile_row0 + li;
+        const bool valid = m < rows_valid;
+        const size_t grow = (size_t)(row0 + m);
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-            const int m = wm * 128 + mt * 32 + li;
-            const bool valid = m < rows_valid;
-            const size_t grow = (size_t)(row0 + m);
+        for (int t = 0; t < HT; ++t) {
+            const int ctile = n0 + wn * HT * 32 + t * 32;  // first h column of the 32-column tile
+            uint32_t hb[8];                                // 16 BF16 values: columns ctile + 16*half + 0..15
 #pragma unroll
-            for (int t = 0; t < HT; ++t) {
-                const int ctile = n0 + wn * HT * 32 + t * 32;  // first h column of the 32-column tile
-                uint32_t hb[8];                                // 16 BF16 values: columns ctile + 16*half + 0..15
-#pragma unroll
-                for (int q = 0; q < 8; ++q) {
-                    const float g0 = acc[mt][t][2 * q], u0 = acc[mt][t + HT][2 * q];
-                    const float g1 = acc[mt][t][2 * q + 1], u1 = acc[mt][t + HT][2 * q + 1];
-                    hb[q] = pack_bf16x2(g0 * u0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)),
-                                        g1 * u1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)));
+            for (int q = 0; q < 8; ++q) {
+                const float g0 = a[t][2 * q], u0 = a[t + HT][2 * q];
+                const float g1 = a[t][2 * q + 1], u1 = a[t + HT][2 * q + 1];
+                hb[q] = pack_bf16x2(g0 * u0 * __builtin_amdgcn_rcpf(1.0f + __expf(-g0)),
+                                    g1 * u1 * __builtin_amdgcn_rcpf(1.0f + __expf(-g1)));
+            }
+            if constexpr (FP4) {
+                const u32x4_t v0 = {hb[0], hb[1], hb[2], hb[3]}, v1 = {hb[4], hb[5], hb[6], hb[7]};
+                uint32_t amax = max(amax_bits8(v0), amax_bits8(v1));
+                amax = max(amax, (uint32_t)__shfl_xor((int)amax, 32));    // the block's other 16 columns
+                const uint32_t byte = e8m0_from_amax(amax);
+                const float scl = scale_operand(byte);
+                const u32x2_t codes = {encode8(v0, scl), encode8(v1, scl)};
+                if (valid) {
+                    *reinterpret_cast<u32x2_t*>(p.out + grow * (size_t)(p.n_out >> 1) + (ctile >> 1) + half * 8) = codes;
+                    if (half == 0) p.outs[scale_byte_offset((long long)grow, ctile >> 5, p.n_out >> 7)] = (uint8_t)byte;
                 }
-                if constexpr (FP4) {
-                    const u32x4_t v0 = {hb[0], hb[1], hb[2], hb[3]}, v1 = {hb[4], hb[5], hb[6], hb[7]};
-                    uint32_t amax = max(amax_bits8(v0), amax_bits8(v1));
-                    amax = max(amax, (uint32_t)__shfl_xor((int)amax, 32));    // the block's other 16 columns
-                    const uint32_t byte = e8m0_from_amax(amax);
-                    const float scl = scale_operand(byte);
-                    const u32x2_t codes = {encode8(v0, scl), encode8(v1, scl)};
-                    if (valid) {
-                        *reinterpret_cast<u32x2_t*>(p.out + grow * (size_t)(p.n_out >> 1) + (ctile >> 1) + half * 8) = codes;
-                        if (half == 0) p.outs[scale_byte_offset((long long)grow, ctile >> 5, p.n_out >> 7)] = (uint8_t)byte;
-                    }
-                } else {
-                    const int tile_row0 = wm * 128 + mt * 32;
-                    store_tile_rows<NT>(p.out + ((size_t)(row0 + tile_row0) * p.n_out + ctile) * 2, (size_t)p.n_out * 2, lane,
-                                        rows_valid - tile_row0, u32x4_t{hb[0], hb[1], hb[2], hb[3]}, u32x4_t{hb[4], hb[5], hb[6], hb[7]});
-                }
+            } else {
+                store_tile_rows<NT>(p.out + ((size_t)(row0 + tile_row0) * p.n_out + ctile) * 2, (size_t)p.n_out * 2, lane,
+                                    rows_valid - tile_row0, u32x4_t{hb[0], hb[1], hb[2], hb[3]}, u32x4_t{hb[4], hb[5], hb[6], hb[7]});
             }
         }
     } else {
+        auto lo8 = [&](int t) __attribute__((always_inline)) {
+            return u32x4_t{pack_bf16x2(a[t][0], a[t][1]), pack_bf16x2(a[t][2], a[t][3]),
+                           pack_bf16x2(a[t][4], a[t][5]), pack_bf16x2(a[t][6], a[t][7])};
+        };
+        auto hi8 = [&](int t) __attribute__((always_inline)) {
+            return u32x4_t{pack_bf16x2(a[t][8], a[t][9]), pack_bf16x2(a[t][10], a[t][11]),
+                           pack_bf16x2(a[t][12], a[t][13]), pack_bf16x2(a[t][14], a[t][15])};
+        };
+        static_assert(WN % 2 == 0, "column tiles are stored in pairs");
 #pragma unroll
-        for (int mt = 0; mt < 4; ++mt) {
-            const int tile_row0 = wm * 128 + mt * 32;
-            auto lo8 = [&](int t) __attribute__((always_inline)) {
-                return u32x4_t{pack_bf16x2(acc[mt][t][0], acc[mt][t][1]), pack_bf16x2(acc[mt][t][2], acc[mt][t][3]),
-                               pack_bf16x2(acc[mt][t][4], acc[mt][t][5]), pack_bf16x2(acc[mt][t][6], acc[mt][t][7])};
-            };
-            auto hi8 = [&](int t) __attribute__((always_inline)) {
-                return u32x4_t{pack_bf16x2(acc[mt][t][8], acc[mt][t][9]), pack_bf16x2(acc[mt][t][10], acc[mt][t][11]),
-                               pack_bf16x2(acc[mt][t][12], acc[mt][t][13]), pack_bf16x2(acc[mt][t][14], acc[mt][t][15])};
-            };
-            static_assert(WN % 2 == 0, "column tiles are stored in pairs");
-#pragma unroll
-            for (int t = 0; t < WN; t += 2) {
-                const int col0 = n0 + wn * WN * 32 + t * 32;
-                store_tile_pair<NT>(p.out + ((size_t)(row0 + tile_row0) * p.n_out + col0) * 2, (size_t)p.n_out * 2, lane,
-                                    rows_valid - tile_row0, lo8(t), hi8(t), lo8(t + 1), hi8(t + 1));
-            }
+        for (int t = 0; t < WN; t += 2) {
+            const int col0 = n0 + wn * WN * 32 + t * 32;
+            store_tile_pair<NT>(p.out + ((size_t)(row0 + tile_row0) * p.n_out + col0) * 2, (size_t)p.n_out * 2, lane,
+                                rows_valid - tile_row0, lo8(t), hi8(t), lo8(t + 1), hi8(t + 1));
         }
     }
+}
+
+// Epilogue of a wave's whole 128-row tile.
+template <bool FP4, bool GATEUP, int WN, bool NT>
+__device__ __forceinline__ void epilogue(const GemmParams& p, v16f_t (&acc)[4][WN], int row0, int rows_valid, int n0,
+                                         int wm, int wn, int li, int half) {
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) epilogue_mt<FP4, GATEUP, WN, NT>(p, acc[mt], mt, row0, rows_valid, n0, wm, wn, li, half);
 }
 
 // Blocks b, b+8, b+16, .. share an XCD (and its L2), so each XCD takes a contiguous range of tiles
