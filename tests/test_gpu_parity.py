@@ -495,6 +495,49 @@ def test_stage_timing_reports_the_stages_of_the_last_call(R, case):
     _sync()
 
 
+@pytest.mark.parametrize("prec", [0, 1])
+def test_shared_expert_runs_as_a_single_group_over_all_tokens(R, prec):
+    """A shared expert (a dense SwiGLU FFN that every token passes through, as both evaluated model families carry
+    beside their routed experts) is the grouped FFN with one group holding all T rows: expert_offsets = [0, T],
+    the token matrix itself as the row matrix.  Checked against the oracle's FFN on the same operands."""
+    from paper_2604_19503_amd.binding import default_config
+    cfg = W.scaled(W.CONFIGS["c2"], T=777, H=512, I=384)
+    rcfg = default_config(cfg.T, cfg.E, cfg.k, cfg.D, cfg.H, cfg.I)
+    ctx = R.Context(rcfg)
+    b = R.LayerBuffers(rcfg, cfg.T)
+    xb, _ = W.gen_tokens(cfg, 41)
+    w13b, w2b = W.gen_weights(cfg, 41, n_experts=1)
+    x, w13, w2 = R.bf16_from_bits(xb), R.bf16_from_bits(w13b), R.bf16_from_bits(w2b)
+    off = np.array([0, cfg.T], dtype=np.int32)
+    b.expert_offsets[:2].copy_(torch.from_numpy(off))
+    b.n_local = 1
+    b.y_rows.fill_(float("nan"))
+    if prec == R.FP4:
+        xq, xs = R.quantize_rows_fp4(x)
+        b.x_q[:cfg.T].copy_(xq); b.x_s.view(-1)[:xs.numel()].copy_(xs.view(-1))
+        ctx.quantize_experts_fp4(w13, w2, b)              # encodes the first expert slot of the buffers
+        ctx.grouped_moe_ffn(R.FP4, w13, w2, b)
+        _sync()
+        oq = [omx.quantize(a) for a in (xb, w13b, w2b)]
+        hq, hs, y = offn.ffn_fp4(oq[0][0], oq[0][1], oq[1][0], oq[1][1], oq[2][0], oq[2][1], off)
+        hq_g = omx.unpack(b.h_mid.view(torch.uint8).reshape(-1)[: b.max_rows * (cfg.I // 2)].reshape(b.max_rows, cfg.I // 2)[:cfg.T].cpu().numpy())
+        hs_g = R.scales_to_canonical(b.h_s, cfg.T, cfg.I)
+        want = offn.down_fp4(hq_g, hs_g, oq[2][0], oq[2][1], off)
+        tol = FP4_TOL
+    else:
+        b.x_perm[:cfg.T].copy_(x)
+        ctx.grouped_moe_ffn(R.BF16, w13, w2, b)
+        _sync()
+        _, want = offn.ffn_bf16(xb, w13b, w2b, off)
+        tol = BF16_TOL
+    got = obf.bits_to_f64(R.bits_from_bf16(b.y_rows[:cfg.T]))
+    worst_row, n_bad, _ = row_report(got, want)
+    _say(f"shared expert prec={prec}: rel fro {rel_fro(got, want):.3e}, worst row {worst_row:.3e}")
+    assert rel_fro(got, want) <= tol and worst_row <= ROW_TOL and n_bad == 0
+    assert torch.isnan(b.y_rows[cfg.T:].float()).all()
+    ctx.close()
+
+
 # ---------------------------------------------------------------------------- edge cases
 def test_edge_empty_batch_and_empty_rank_and_empty_expert(R):
     from paper_2604_19503_amd.binding import default_config
