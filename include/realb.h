@@ -235,8 +235,9 @@ typedef struct {
     int rank; int force;
     int overlap;                                /* weight encoding: 0 = on `stream`, 1 = on the context's side stream,
                                                    2 = skipped (w13_q .. w2_s already hold this layer's encoded weights),
-                                                   3 = speculative (realb_layer_forward only): issued on the side stream
-                                                       BEFORE routing, so that it fills the wait for the host's decision;
+                                                   3 = speculative (realb_layer_forward only): W13's is issued on the side
+                                                       stream BEFORE routing, so that it fills the wait for the host's
+                                                       decision, W2's on `stream` once the decision is FP4; W13's is
                                                        unused if the decision is BF16 (in modes 3 and 4 the activations
                                                        of all T tokens are encoded there ahead of the decision as well),
                                                    4 = prefetched: w13_q .. w2_s are being filled by the previous call's

@@ -26,7 +26,6 @@ struct Ctx {
     int32_t* stats_host;   // [2*D]
     hipStream_t side;      // side stream for the weight encoder
     hipEvent_t ev_fork, ev_join;
-    hipEvent_t ev_gate;       // speculative mode: activations and W13 are encoded (what the gate/up GEMM needs); ev_join: W2 as well
     hipEvent_t ev_prefetch;   // end of the last cross-layer prefetch on the side stream
     bool prefetch_pending;    // ev_prefetch has been recorded and not yet been waited for by a caller's stream
     int gemm_reserve;         // compute units the grouped GEMMs' persistent grids leave free (set around a prefetching call)

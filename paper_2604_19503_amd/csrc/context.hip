@@ -109,7 +109,7 @@ int realb_create(const realb_config* cfg, realb_ctx** out) {
     c->cfg = *cfg;
     c->n_local = cfg->E / cfg->D;
     c->M = cfg->M_init;
-    c->wave_cnt = nullptr; c->hist_part = nullptr; c->stats_host = nullptr; c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr; c->ev_gate = nullptr; c->ev_stats = nullptr; c->ev_prefetch = nullptr; c->prefetch_pending = false; c->gemm_reserve = 0; c->stage_timing = false; c->stage_valid = false;
+    c->wave_cnt = nullptr; c->hist_part = nullptr; c->stats_host = nullptr; c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr; c->ev_stats = nullptr; c->ev_prefetch = nullptr; c->prefetch_pending = false; c->gemm_reserve = 0; c->stage_timing = false; c->stage_valid = false;
     for (auto& ev : c->stage_ev) ev = nullptr;
     hipError_t e = hipGetDevice(&c->device);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&c->num_cus, hipDeviceAttributeMultiprocessorCount, c->device);
@@ -120,7 +120,6 @@ int realb_create(const realb_config* cfg, realb_ctx** out) {
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_gate, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_stats, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_prefetch, hipEventDisableTiming);
     if (e != hipSuccess) {
@@ -145,7 +144,6 @@ int realb_destroy(realb_ctx* ctx) {
     if (c->stats_host) (void)hipHostFree(c->stats_host);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
-    if (c->ev_gate) (void)hipEventDestroy(c->ev_gate);
     if (c->ev_stats) (void)hipEventDestroy(c->ev_stats);
     if (c->ev_prefetch) (void)hipEventDestroy(c->ev_prefetch);
     for (auto& ev : c->stage_ev)

@@ -92,10 +92,14 @@ static int rank_forward_steps(realb_ctx* ctx, realb_layer_io* io, int prec, void
         rc = permute_gather(c, io->x, io->assign_to_row, io->T, prec, io->x_perm, io->x_q, io->x_s, s, gather ? 1 : 0);
         if (rc != REALB_OK) return rc;
     }
-    // speculative weights: the gate/up GEMM needs the activations and W13 only (ev_gate); W2's encoding may still run beside it
-    const bool split_join = fp4 && quant_in_flight && gather;
-    if (split_join) REALB_HIP(hipStreamWaitEvent(s, c->ev_gate, 0));
-    else if (fp4 && ((side && !encoded) || act_in_flight)) REALB_HIP(hipStreamWaitEvent(s, c->ev_join, 0));
+    // speculative mode: what went to the side stream ahead of the decision is what the gate/up GEMM needs (activations, W13);
+    // W2 is encoded here, on the caller's stream, while that is still in flight -- the caller's stream would idle until the join
+    // anyway, a BF16 decision never pays for it, and the down GEMM then needs no second cross-stream wait (each costs microseconds).
+    if (fp4 && quant_in_flight) {
+        rc = launch_quantize_flat(io->w2, (long long)c->n_local * c->cfg.H, c->cfg.I, io->w2_q, io->w2_s, nullptr, 0, 0, nullptr, nullptr, s);
+        if (rc != REALB_OK) return rc;
+    }
+    if (fp4 && ((side && !encoded) || act_in_flight)) REALB_HIP(hipStreamWaitEvent(s, c->ev_join, 0));
     if (prefetch) {
         REALB_HIP(hipEventRecord(c->ev_fork, s));         // the prefetch may start once the stream is here, beside the GEMMs
         c->gemm_reserve = io->reserve_cus;
@@ -117,7 +121,6 @@ static int rank_forward_steps(realb_ctx* ctx, realb_layer_io* io, int prec, void
         stage_mark(c, s, 5);
         rc = issue_prefetch();
         if (rc != REALB_OK) return rc;
-        if (split_join) REALB_HIP(hipStreamWaitEvent(s, c->ev_join, 0));
         rc = realb_grouped_moe_ffn_down(ctx, prec, io->expert_offsets, c->n_local, io->max_rows, io->h_mid, fp4 ? io->h_s : nullptr,
                                         fp4 ? (const void*)io->w2_q : io->w2, fp4 ? io->w2_s : nullptr, io->y_rows, stream);
     } else if (fp4) {
@@ -190,15 +193,11 @@ extern "C" int realb_layer_forward(realb_ctx* ctx, realb_layer_io* io, void* str
         REALB_HIP(hipEventRecord(c->ev_fork, s));
         REALB_HIP(hipStreamWaitEvent(c->side, c->ev_fork, 0));
         rc = REALB_OK;
-        // side stream, in the order the GEMMs need them: activations, W13 (-> ev_gate), W2 (-> ev_join)
+        // side stream: what the gate/up GEMM needs -- the activations and W13 (W2 follows on the caller's stream, after the decision)
         if (spec_x) rc = launch_quantize_flat(io->x, io->T, c->cfg.H, io->x_q, io->x_s, nullptr, 0, 0, nullptr, nullptr, c->side);
         if (rc == REALB_OK && spec_w)
             rc = launch_quantize_flat(io->w13, (long long)c->n_local * 2 * c->cfg.I, c->cfg.H, io->w13_q, io->w13_s, nullptr, 0, 0, nullptr,
                                       nullptr, c->side);
-        REALB_HIP(hipEventRecord(c->ev_gate, c->side));
-        if (rc == REALB_OK && spec_w)
-            rc = launch_quantize_flat(io->w2, (long long)c->n_local * c->cfg.H, c->cfg.I, io->w2_q, io->w2_s, nullptr, 0, 0, nullptr, nullptr,
-                                      c->side);
         REALB_HIP(hipEventRecord(c->ev_join, c->side));
         if (rc != REALB_OK) { (void)hipStreamWaitEvent(s, c->ev_join, 0); return rc; }
     }
