@@ -19,11 +19,15 @@ struct Ctx {
     int num_cus;
     double M;
     // device workspace
-    int32_t* wave_cnt;     // [n_chunks_max, n_local]  per-chunk local-expert counts, then exclusive bases
+    int32_t* wave_cnt;     // [n_local, n_chunks]  per-chunk local-expert counts of the permutation (one allocation with group_cnt)
+    int32_t* group_cnt;    // [n_local, n_groups]  the same summed over groups of 16 chunks
     int n_chunks_max;
     int32_t* hist_part;    // [kRouteBlocksMax, 2*E]  per-block partial histograms of route_stats
     // pinned host staging for the policy's inputs
-    int32_t* stats_host;   // [2*D]
+    int32_t* stats_host;   // [2*D]: rank loads, rank vision loads (copy target of realb_select_precision)
+    unsigned long long* stats_words;   // [2*D], host-coherent: the same, written by the layer call's reduce block, each word
+                                       // tagged with the call's sequence number (see hist_reduce_body)
+    int stats_seq;         // sequence number of the last layer call's statistics (never 0)
     hipStream_t side;      // side stream for the weight encoder
     hipEvent_t ev_fork, ev_join;
     hipEvent_t ev_prefetch;   // end of the last cross-layer prefetch on the side stream
@@ -33,13 +37,12 @@ struct Ctx {
     bool stage_timing;
     bool stage_valid;      // a whole layer call has recorded all boundaries since timing was switched on
     hipEvent_t stage_ev[REALB_N_STAGES + 1];
-    hipEvent_t ev_stats;   // recorded behind the histogram reduce: the host's cue that the routing statistics are in stats_host
 };
 
 void set_error(const char* fmt, ...);
-// Waits for `ready` (an event recorded behind the kernel that fills stats_host), then evaluates the policy.
+// Waits until the reduce block launched on `s` has written the statistics tagged `seq` to stats_words, then evaluates the policy.
 int select_precision_pinned(Ctx* c, int T, int force, int32_t* prec_host, double* ib_global_host, double* M_after_host,
-                            hipEvent_t ready);
+                            int seq, hipStream_t s);
 int permute_indices(Ctx* c, const int32_t* topk_ids, int T, int rank, long long max_rows, int32_t* expert_offsets,
                     int32_t* row_to_assign, int32_t* assign_to_row, hipStream_t s);
 int launch_gate_up_bf16_gather(Ctx* c, const int32_t* expert_offsets, int n_local, long long max_rows, const void* x, int T,
@@ -51,7 +54,7 @@ int launch_gate_up_fp4_gather(Ctx* c, const int32_t* expert_offsets, int n_local
 int route_topk_only(Ctx* c, const float* logits, const uint8_t* is_vision, int T, int32_t* topk_ids, float* topk_w, hipStream_t s);
 int route_and_index(Ctx* c, const float* logits, const uint8_t* is_vision, int T, int rank, long long max_rows, int32_t* topk_ids,
                     float* topk_w, int32_t* expert_cnt, int32_t* expert_vis, int32_t* rank_load, int32_t* rank_vis,
-                    int32_t* expert_offsets, int32_t* row_to_assign, int32_t* assign_to_row, hipEvent_t stats_ready, hipStream_t s);
+                    int32_t* expert_offsets, int32_t* row_to_assign, int32_t* assign_to_row, int stats_seq, hipStream_t s);
 int permute_gather(Ctx* c, const void* x, const int32_t* assign_to_row, int T, int prec, void* x_perm, uint8_t* x_q,
                    uint8_t* x_s, hipStream_t s, int token_major);
 // BF16 -> MXFP4 encoder on one matrix [rows0, K0], or two when rows1 > 0, in a single launch.

@@ -37,7 +37,9 @@ static int check_shape(const realb_config* c) {
 
 // The two device buffers of a context's workspace.
 static int n_chunks_max(const realb_config* c) { return ceil_div((long long)c->T_max * c->k, kPermChunk) + 1; }
-static size_t wave_cnt_bytes(const realb_config* c) { return (size_t)n_chunks_max(c) * (c->E / c->D) * sizeof(int32_t); }
+static size_t wave_cnt_bytes(const realb_config* c) {      // chunk counts, then the sums over groups of 16 chunks
+    return ((size_t)n_chunks_max(c) + ceil_div(n_chunks_max(c), 16)) * (c->E / c->D) * sizeof(int32_t);
+}
 static size_t hist_part_bytes(const realb_config* c) { return (size_t)kRouteBlocksMax * 2 * c->E * sizeof(int32_t); }
 
 // Precision policy (paper Sec. "Real-time Modality-aware LB Scheduling" and "LB
@@ -74,10 +76,32 @@ static void policy(const realb_config& c, const int32_t* load, const int32_t* vi
     *M_inout = M_new;
 }
 
-// Policy on the pinned host copy of the statistics that the last realb_route_stats on `stream` wrote.
+// Policy on the pinned host copy of the statistics.  The reduce block of the kernel launched on `s` writes them as
+// 64-bit words whose upper halves carry `seq`; the host polls until every word shows it.  Every few thousand polls it
+// also asks the stream: a stream that has drained (or failed) without the words arriving ends the wait with an
+// error instead of a hang.
 int select_precision_pinned(Ctx* c, int T, int force, int32_t* prec_host, double* ib_global_host, double* M_after_host,
-                            hipEvent_t ready) {
-    REALB_HIP(hipEventSynchronize(ready));
+                            int seq, hipStream_t s) {
+    const int n = 2 * c->cfg.D;
+    auto arrived = [&]() {
+        for (int i = 0; i < n; ++i) {
+            const unsigned long long w = __atomic_load_n(c->stats_words + i, __ATOMIC_ACQUIRE);
+            if ((uint32_t)(w >> 32) != (uint32_t)seq) return false;
+            c->stats_host[i] = (int32_t)(uint32_t)w;
+        }
+        return true;
+    };
+    for (unsigned spin = 1; !arrived(); ++spin) {
+        if ((spin & 0xFFF) == 0) {
+            const hipError_t q = hipStreamQuery(s);
+            if (q == hipSuccess) {                        // everything enqueued has run: the words must be there now
+                REALB_REQUIRE(arrived(), REALB_EHIP, "routing statistics never reached the host");
+                break;
+            }
+            if (q != hipErrorNotReady) REALB_HIP(q);
+        }
+        __builtin_ia32_pause();
+    }
     policy(c->cfg, c->stats_host, c->stats_host + c->cfg.D, T, force, &c->M, prec_host, ib_global_host);
     if (M_after_host) *M_after_host = c->M;
     return REALB_OK;
@@ -109,18 +133,20 @@ int realb_create(const realb_config* cfg, realb_ctx** out) {
     c->cfg = *cfg;
     c->n_local = cfg->E / cfg->D;
     c->M = cfg->M_init;
-    c->wave_cnt = nullptr; c->hist_part = nullptr; c->stats_host = nullptr; c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr; c->ev_stats = nullptr; c->ev_prefetch = nullptr; c->prefetch_pending = false; c->gemm_reserve = 0; c->stage_timing = false; c->stage_valid = false;
+    c->wave_cnt = nullptr; c->group_cnt = nullptr; c->hist_part = nullptr; c->stats_host = nullptr; c->stats_words = nullptr; c->side = nullptr; c->ev_fork = nullptr; c->ev_join = nullptr; c->stats_seq = 0; c->ev_prefetch = nullptr; c->prefetch_pending = false; c->gemm_reserve = 0; c->stage_timing = false; c->stage_valid = false;
     for (auto& ev : c->stage_ev) ev = nullptr;
     hipError_t e = hipGetDevice(&c->device);
     if (e == hipSuccess) e = hipDeviceGetAttribute(&c->num_cus, hipDeviceAttributeMultiprocessorCount, c->device);
     c->n_chunks_max = n_chunks_max(cfg);
     if (e == hipSuccess) e = hipMalloc((void**)&c->wave_cnt, wave_cnt_bytes(cfg));
+    if (e == hipSuccess) c->group_cnt = c->wave_cnt + (size_t)c->n_chunks_max * c->n_local;
     if (e == hipSuccess) e = hipMalloc((void**)&c->hist_part, hist_part_bytes(cfg));
     if (e == hipSuccess) e = hipHostMalloc((void**)&c->stats_host, 2 * cfg->D * sizeof(int32_t), hipHostMallocDefault);
+    if (e == hipSuccess) e = hipHostMalloc((void**)&c->stats_words, 2 * cfg->D * sizeof(unsigned long long), hipHostMallocCoherent);
+    if (e == hipSuccess) memset(c->stats_words, 0, 2 * cfg->D * sizeof(unsigned long long));
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&c->side, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_fork, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_join, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_stats, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&c->ev_prefetch, hipEventDisableTiming);
     if (e != hipSuccess) {
         realb_destroy(reinterpret_cast<realb_ctx*>(c));
@@ -142,9 +168,9 @@ int realb_destroy(realb_ctx* ctx) {
     if (c->wave_cnt) (void)hipFree(c->wave_cnt);
     if (c->hist_part) (void)hipFree(c->hist_part);
     if (c->stats_host) (void)hipHostFree(c->stats_host);
+    if (c->stats_words) (void)hipHostFree(c->stats_words);
     if (c->ev_fork) (void)hipEventDestroy(c->ev_fork);
     if (c->ev_join) (void)hipEventDestroy(c->ev_join);
-    if (c->ev_stats) (void)hipEventDestroy(c->ev_stats);
     if (c->ev_prefetch) (void)hipEventDestroy(c->ev_prefetch);
     for (auto& ev : c->stage_ev)
         if (ev) (void)hipEventDestroy(ev);

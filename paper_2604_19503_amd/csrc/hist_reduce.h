@@ -6,15 +6,19 @@
 
 namespace realb {
 
-// Adds up the blocks' partial histograms and the per-rank sums (also written to the context's pinned
-// host buffer, which realb_layer_forward reads after one stream synchronisation) (a separate launch: the kernel
-// boundary makes the partials of all XCDs visible).  Thread layout: counter c = tid % CW,
+// Adds up the blocks' partial histograms and the per-rank sums (a separate launch: the kernel boundary makes the
+// partials of all XCDs visible).  With stats_words != NULL the per-rank sums also go to the context's pinned,
+// host-coherent buffer stats_words [2*D] (loads, then vision loads), each as one 64-bit word that carries stats_seq in
+// its upper half: the host polls until every word shows the sequence number of its call, so realb_layer_forward
+// learns the statistics a few microseconds after this block has them -- without an event behind the kernel, without
+// waiting for the kernel's other blocks, and without a fence (every word validates itself).
+// Thread layout: counter c = tid % CW,
 // slice = tid / CW; each slice walks its share of the partials, LDS atomics merge the slices.
 // tot: 2*E ints of LDS.
 __device__ __forceinline__ void hist_reduce_body(int32_t* tot, const int32_t* __restrict__ hist_part, int n_part, int E, int D,
                                                  int32_t* __restrict__ expert_cnt, int32_t* __restrict__ expert_vis,
                                                  int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis,
-                                                 int32_t* __restrict__ stats_host) {
+                                                 unsigned long long* __restrict__ stats_words, int stats_seq) {
     const int C2 = 2 * E;
     for (int i = threadIdx.x; i < C2; i += blockDim.x) tot[i] = 0;
     __syncthreads();
@@ -43,9 +47,10 @@ __device__ __forceinline__ void hist_reduce_body(int32_t* tot, const int32_t* __
         for (int e = 0; e < n_local; ++e) { load += tot[d * n_local + e]; vis += tot[E + d * n_local + e]; }
         rank_load[d] = load;
         rank_vis[d] = vis;
-        if (stats_host) {                             // pinned host copy for the policy: saves two copy launches
-            stats_host[d] = load;
-            stats_host[D + d] = vis;
+        if (stats_words) {                            // pinned host copy for the policy: no copy launches, no event
+            const unsigned long long tag = (unsigned long long)(uint32_t)stats_seq << 32;
+            __hip_atomic_store(stats_words + d, tag | (uint32_t)load, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            __hip_atomic_store(stats_words + D + d, tag | (uint32_t)vis, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         }
     }
 }

@@ -204,17 +204,18 @@ extern "C" int realb_layer_forward(realb_ctx* ctx, realb_layer_io* io, void* str
     // an error between here and rank_forward_impl (which joins by itself) still joins the side stream
     auto fail = [&](int code) { if (speculative) (void)hipStreamWaitEvent(as_stream(stream), c->ev_join, 0); return code; };
     stage_mark(c, as_stream(stream), 0);
-    // The statistics reach pinned host memory with the histogram reduce.  The permutation's index kernels do not
-    // depend on the precision, so they are interleaved with the routing kernels (the reduce shares a launch with
-    // the permutation's count kernel) and the last two of them run while the host waits for the event, takes the
-    // decision and launches the rest.
+    // The statistics reach pinned host memory with the histogram reduce, which then publishes this call's sequence
+    // number there.  The permutation's index kernels do not depend on the precision, so they are interleaved with the
+    // routing kernels (the reduce shares a launch with the permutation's count kernel) and the ranking kernel runs
+    // while the host polls for the number, takes the decision and launches the rest.
+    if (++c->stats_seq <= 0) c->stats_seq = 1;
     rc = route_and_index(c, io->logits, io->is_vision, io->T, io->rank, io->max_rows, io->topk_ids, io->topk_w, io->expert_cnt,
                          io->expert_vis, io->rank_load, io->rank_vis, io->expert_offsets, io->row_to_assign, io->assign_to_row,
-                         c->ev_stats, as_stream(stream));
+                         c->stats_seq, as_stream(stream));
     if (rc != REALB_OK) return fail(rc);
     stage_mark(c, as_stream(stream), 1);
     stage_mark(c, as_stream(stream), 2);
-    rc = select_precision_pinned(c, io->T, io->force, io->prec_host, &io->ib_global, &io->M_after, c->ev_stats);
+    rc = select_precision_pinned(c, io->T, io->force, io->prec_host, &io->ib_global, &io->M_after, c->stats_seq, as_stream(stream));
     if (rc != REALB_OK) return fail(rc);
     return rank_forward_impl(ctx, io, io->prec_host[io->rank], stream, spec_w, spec_x, true);
 }

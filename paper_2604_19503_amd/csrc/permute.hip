@@ -10,38 +10,11 @@
 namespace realb {
 
 constexpr int kIters = kPermChunk / 64;   // 64 assignments per wave iteration
-
-// Phase 1: each wave counts, per local expert, the assignments of its chunk of
-// kPermChunk consecutive flat indices a = t*k + j.  Lane e holds expert e's count.
-__device__ __forceinline__ void perm_count_body(int chunk, const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
-                                                int n_chunks, int32_t* __restrict__ wave_cnt) {
-    const int lane = threadIdx.x & 63;
-    if (chunk >= n_chunks) return;
-    const int begin = chunk * kPermChunk;
-    int le[kIters];
-#pragma unroll
-    for (int i = 0; i < kIters; ++i) {
-        const int a = begin + i * 64 + lane;
-        le[i] = (a < A) ? topk_ids[a] - lo : -1;
-    }
-    int cnt = 0;
-#pragma unroll
-    for (int i = 0; i < kIters; ++i)
-        for (int e = 0; e < n_local; ++e) {
-            const unsigned long long m = __ballot(le[i] == e);
-            if (lane == e) cnt += __popcll(m);
-        }
-    if (lane < n_local) wave_cnt[(size_t)lane * n_chunks + chunk] = cnt;     // expert-major: the scan reads a column contiguously
-}
-
-__global__ void __launch_bounds__(256) perm_count_kernel(const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
-                                                         int n_chunks, int32_t* __restrict__ wave_cnt) {
-    perm_count_body(blockIdx.x * 4 + (threadIdx.x >> 6), topk_ids, A, lo, n_local, n_chunks, wave_cnt);
-}
+constexpr int kGroup = 16;                // chunks (= waves) per block of the count and rank kernels
 
 // Inclusive prefix sum over the 64 lanes with DPP only: four shifts inside each row of 16 lanes, then the
 // last lane of row 0 / row 2 is added to the following row, then lane 31 to the upper half.
-__device__ __forceinline__ int wave_inclusive_scan(int v, int /*lane*/) {
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
     v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, false);     // row_shr:1
     v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, false);     // row_shr:2
     v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, false);     // row_shr:4
@@ -50,87 +23,119 @@ __device__ __forceinline__ int wave_inclusive_scan(int v, int /*lane*/) {
     v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);     // row_bcast:31 into rows 2 and 3
     return v;
 }
+__device__ __forceinline__ int wave_sum(int v) { return __builtin_amdgcn_readlane(wave_inclusive_scan(v), 63); }
 
-// Phase 2 (one block): per expert, exclusive scan of the chunk counts in chunk
-// order (in place: counts become the chunk's first rank within the expert), then
-// the exclusive scan over experts gives expert_offsets.  A wave takes an expert and walks its
-// column 64 chunks at a time; the loads of up to 16 such steps are issued together (one memory
-// latency instead of one per step), then the steps are scanned in order with a running carry.
-// totals: 64 ints of LDS.
-__device__ __forceinline__ void perm_scan_body(int* totals, int32_t* __restrict__ wave_cnt, int n_chunks, int n_local,
-                                               int32_t* __restrict__ expert_offsets) {
-    constexpr int BATCH = 16;
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int n_waves = blockDim.x >> 6;
-    for (int e = wave; e < n_local; e += n_waves) {
-        int carry = 0;
-        for (int c0 = 0; c0 < n_chunks; c0 += 64 * BATCH) {
-            int v[BATCH];
+// The local expert (or -1) of each of the 4 x 64 assignments a = t*k + j of a wave's chunk.
+__device__ __forceinline__ void load_chunk(int (&le)[kIters], const int32_t* __restrict__ topk_ids, int chunk, int n_chunks, int A,
+                                           int lo, int lane) {
 #pragma unroll
-            for (int i = 0; i < BATCH; ++i) {
-                const int c = c0 + i * 64 + lane;
-                v[i] = (c < n_chunks) ? wave_cnt[(size_t)e * n_chunks + c] : 0;
-            }
-#pragma unroll
-            for (int i = 0; i < BATCH; ++i) {
-                const int c = c0 + i * 64 + lane;
-                const int incl = wave_inclusive_scan(v[i], lane);
-                if (c < n_chunks) wave_cnt[(size_t)e * n_chunks + c] = carry + incl - v[i];
-                carry += __builtin_amdgcn_readlane(incl, 63);
-            }
-        }
-        if (lane == 0) totals[e] = carry;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int run = 0;
-        for (int e = 0; e < n_local; ++e) { expert_offsets[e] = run; run += totals[e]; }
-        expert_offsets[n_local] = run;
+    for (int i = 0; i < kIters; ++i) {
+        const int a = chunk * kPermChunk + i * 64 + lane;
+        le[i] = (chunk < n_chunks && a < A) ? topk_ids[a] - lo : -1;
     }
 }
 
-__global__ void __launch_bounds__(1024) perm_scan_kernel(int32_t* __restrict__ wave_cnt, int n_chunks, int n_local,
-                                                         int32_t* __restrict__ expert_offsets) {
-    __shared__ int totals[64];
-    perm_scan_body(totals, wave_cnt, n_chunks, n_local, expert_offsets);
+// Phase 1 (a block = one group of kGroup chunks, one wave per chunk): each wave counts, per local expert, the
+// assignments of its chunk of kPermChunk consecutive flat indices (lane e holds expert e's count); the block adds
+// them up per expert.  wave_cnt is expert-major [n_local, n_chunks], group_cnt [n_local, n_groups].
+// gsum: 64 ints of LDS.
+__device__ __forceinline__ void perm_count_body(int* gsum, int group, const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
+                                                int n_chunks, int n_groups, int32_t* __restrict__ wave_cnt,
+                                                int32_t* __restrict__ group_cnt) {
+    const int lane = threadIdx.x & 63;
+    const int chunk = group * kGroup + (threadIdx.x >> 6);
+    int le[kIters];
+    load_chunk(le, topk_ids, chunk, n_chunks, A, lo, lane);
+    if (threadIdx.x < 64) gsum[threadIdx.x] = 0;
+    __syncthreads();
+    int cnt = 0;
+#pragma unroll
+    for (int i = 0; i < kIters; ++i)
+        for (int e = 0; e < n_local; ++e) {
+            const unsigned long long m = __ballot(le[i] == e);
+            if (lane == e) cnt += __popcll(m);
+        }
+    if (chunk < n_chunks && lane < n_local) {
+        wave_cnt[(size_t)lane * n_chunks + chunk] = cnt;
+        atomicAdd(&gsum[lane], cnt);
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < n_local) group_cnt[(size_t)threadIdx.x * n_groups + group] = gsum[threadIdx.x];
+}
+
+__global__ void __launch_bounds__(64 * kGroup) perm_count_kernel(const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
+                                                                  int n_chunks, int n_groups, int32_t* __restrict__ wave_cnt,
+                                                                  int32_t* __restrict__ group_cnt) {
+    __shared__ int gsum[64];
+    perm_count_body(gsum, blockIdx.x, topk_ids, A, lo, n_local, n_chunks, n_groups, wave_cnt, group_cnt);
 }
 
 // The layer call's histogram reduce shares a launch with the permutation's count kernel: block 0 adds up the routing
-// kernel's partial histograms (and hands the per-rank statistics to the host), the other blocks count their chunks,
-// 16 per block.  One kernel boundary less on a path made of short, latency-bound kernels, and the host learns the
-// statistics two kernels (scan, rank) before the stream runs dry.
-__global__ void __launch_bounds__(1024) reduce_and_count_kernel(const int32_t* __restrict__ hist_part, int n_part, int E, int D,
-                                                                int32_t* __restrict__ expert_cnt, int32_t* __restrict__ expert_vis,
-                                                                int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis,
-                                                                int32_t* __restrict__ stats_host, const int32_t* __restrict__ topk_ids,
-                                                                int A, int lo, int n_local, int n_chunks, int32_t* __restrict__ wave_cnt) {
+// kernel's partial histograms (and hands the per-rank statistics to the host), the other blocks count their groups of
+// chunks.  One kernel boundary less on a path made of short, latency-bound kernels.
+__global__ void __launch_bounds__(64 * kGroup) reduce_and_count_kernel(const int32_t* __restrict__ hist_part, int n_part, int E, int D,
+                                                                        int32_t* __restrict__ expert_cnt, int32_t* __restrict__ expert_vis,
+                                                                        int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis,
+                                                                        unsigned long long* __restrict__ stats_words, int stats_seq,
+                                                                        const int32_t* __restrict__ topk_ids,
+                                                                        int A, int lo, int n_local, int n_chunks, int n_groups,
+                                                                        int32_t* __restrict__ wave_cnt, int32_t* __restrict__ group_cnt) {
     extern __shared__ int32_t dyn[];                  // 2*E ints (block 0 only)
-    if (blockIdx.x == 0) hist_reduce_body(dyn, hist_part, n_part, E, D, expert_cnt, expert_vis, rank_load, rank_vis, stats_host);
-    else perm_count_body((blockIdx.x - 1) * 16 + (threadIdx.x >> 6), topk_ids, A, lo, n_local, n_chunks, wave_cnt);
+    __shared__ int gsum[64];
+    if (blockIdx.x == 0) hist_reduce_body(dyn, hist_part, n_part, E, D, expert_cnt, expert_vis, rank_load, rank_vis, stats_words, stats_seq);
+    else perm_count_body(gsum, blockIdx.x - 1, topk_ids, A, lo, n_local, n_chunks, n_groups, wave_cnt, group_cnt);
 }
 
-// Phase 3: each wave walks its chunk again and gives every local assignment its
-// row: expert_offsets[e] + (rank of the chunk's first) + (rank inside the chunk).
-__global__ void __launch_bounds__(256) perm_rank_kernel(const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
-                                                        int n_chunks, const int32_t* __restrict__ wave_cnt,
-                                                        const int32_t* __restrict__ expert_offsets,
-                                                        int32_t* __restrict__ row_to_assign, int32_t* __restrict__ assign_to_row) {
-    const int lane = threadIdx.x & 63;
-    const int chunk = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (chunk >= n_chunks) return;
-    const int begin = chunk * kPermChunk;
+// Phase 2 (same blocks): every block first works out, from the group sums, each expert's total (whose exclusive scan
+// over the experts is expert_offsets; block 0 stores it) and the number of its assignments in earlier groups -- wave w
+// adds up expert w's column of group_cnt, 64 groups per step -- so no separate scan kernel sits between the two
+// phases.  Then each wave walks its chunk again and gives every local assignment its row:
+// expert_offsets[e] + (assignments of e in earlier groups) + (in earlier chunks of the group) + (rank inside the chunk).
+__global__ void __launch_bounds__(64 * kGroup) perm_rank_kernel(const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
+                                                                 int n_chunks, int n_groups, const int32_t* __restrict__ wave_cnt,
+                                                                 const int32_t* __restrict__ group_cnt,
+                                                                 int32_t* __restrict__ expert_offsets,
+                                                                 int32_t* __restrict__ row_to_assign, int32_t* __restrict__ assign_to_row) {
+    __shared__ int before[64], total[64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int group = blockIdx.x;
+    const int chunk = group * kGroup + wave;
     int le[kIters];
+    load_chunk(le, topk_ids, chunk, n_chunks, A, lo, lane);
+    // this lane's expert: its assignments in the earlier chunks of this group
+    int within = 0;
+    if (lane < n_local) {
+        int v[kGroup];
 #pragma unroll
-    for (int i = 0; i < kIters; ++i) {
-        const int a = begin + i * 64 + lane;
-        le[i] = (a < A) ? topk_ids[a] - lo : -1;
+        for (int q = 0; q < kGroup; ++q)                     // (q < wave: chunk group*kGroup + q exists whenever this wave's chunk does)
+            v[q] = (q < wave && group * kGroup + q < n_chunks) ? wave_cnt[(size_t)lane * n_chunks + group * kGroup + q] : 0;
+#pragma unroll
+        for (int q = 0; q < kGroup; ++q) within += v[q];
     }
-    int running = (lane < n_local) ? expert_offsets[lane] + wave_cnt[(size_t)lane * n_chunks + chunk] : 0;
+    for (int e = wave; e < n_local; e += kGroup) {
+        int b = 0, t = 0;
+        for (int q = lane; q < n_groups; q += 64) {
+            const int v = group_cnt[(size_t)e * n_groups + q];
+            t += v;
+            if (q < group) b += v;
+        }
+        b = wave_sum(b);
+        t = wave_sum(t);
+        if (lane == 0) { before[e] = b; total[e] = t; }
+    }
+    __syncthreads();
+    const int tot = lane < n_local ? total[lane] : 0;
+    const int incl = wave_inclusive_scan(tot);
+    if (group == 0 && wave == 0) {
+        if (lane < n_local) expert_offsets[lane] = incl - tot;
+        if (lane == n_local - 1) expert_offsets[n_local] = incl;
+    }
+    if (chunk >= n_chunks) return;
+    int running = (lane < n_local) ? incl - tot + before[lane] + within : 0;
     const unsigned long long lt_mask = (1ull << lane) - 1ull;
 #pragma unroll
     for (int i = 0; i < kIters; ++i) {
-        const int a = begin + i * 64 + lane;
+        const int a = chunk * kPermChunk + i * 64 + lane;
         int row = -1;
         for (int e = 0; e < n_local; ++e) {
             const unsigned long long m = __ballot(le[i] == e);
@@ -245,24 +250,23 @@ int permute_indices(Ctx* c, const int32_t* topk_ids, int T, int rank, long long 
     REALB_REQUIRE(max_rows >= worst, REALB_EINVAL, "max_rows=%lld is below the worst case %lld", max_rows, worst);
     REALB_REQUIRE(T == 0 || (topk_ids && row_to_assign && assign_to_row), REALB_EINVAL, "NULL argument");
     const int n_chunks = ceil_div(A, kPermChunk);
+    const int n_groups = ceil_div(n_chunks, kGroup);
     const int lo = rank * n_local;
-    const int chunk_blocks = ceil_div(n_chunks, 4);
-    if (n_chunks > 0)
-        hipLaunchKernelGGL(perm_count_kernel, dim3(chunk_blocks), dim3(256), 0, s, topk_ids, (int)A, lo, n_local, n_chunks, c->wave_cnt);
-    hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, s, c->wave_cnt, n_chunks, n_local, expert_offsets);
-    if (n_chunks > 0)
-        hipLaunchKernelGGL(perm_rank_kernel, dim3(chunk_blocks), dim3(256), 0, s, topk_ids, (int)A, lo, n_local, n_chunks,
-                           c->wave_cnt, expert_offsets, row_to_assign, assign_to_row);
+    if (n_groups > 0)
+        hipLaunchKernelGGL(perm_count_kernel, dim3(n_groups), dim3(64 * kGroup), 0, s, topk_ids, (int)A, lo, n_local, n_chunks, n_groups,
+                           c->wave_cnt, c->group_cnt);
+    hipLaunchKernelGGL(perm_rank_kernel, dim3(n_groups > 0 ? n_groups : 1), dim3(64 * kGroup), 0, s, topk_ids, (int)A, lo, n_local,
+                       n_chunks, n_groups, c->wave_cnt, c->group_cnt, expert_offsets, row_to_assign, assign_to_row);
     REALB_HIP(hipGetLastError());
     return REALB_OK;
 }
 
 // Routing and the permutation's index kernels as the layer call issues them: top-k + histograms, then
-// [histogram reduce | chunk counts] in one launch, then -- behind the event that tells the host the statistics have
-// reached pinned memory -- the scan and the ranking kernel, which run while the host takes the decision.
+// [histogram reduce | chunk counts] in one launch -- whose reduce block writes the statistics, tagged with stats_seq,
+// to pinned memory -- then the ranking kernel, which runs while the host takes the decision.
 int route_and_index(Ctx* c, const float* logits, const uint8_t* is_vision, int T, int rank, long long max_rows, int32_t* topk_ids,
                     float* topk_w, int32_t* expert_cnt, int32_t* expert_vis, int32_t* rank_load, int32_t* rank_vis,
-                    int32_t* expert_offsets, int32_t* row_to_assign, int32_t* assign_to_row, hipEvent_t stats_ready, hipStream_t s) {
+                    int32_t* expert_offsets, int32_t* row_to_assign, int32_t* assign_to_row, int stats_seq, hipStream_t s) {
     REALB_REQUIRE(c && expert_cnt && expert_vis && rank_load && rank_vis && expert_offsets, REALB_EINVAL, "NULL argument");
     REALB_REQUIRE(T >= 0 && T <= c->cfg.T_max, REALB_ECAP, "T=%d outside [0, T_max=%d]", T, c->cfg.T_max);
     REALB_REQUIRE(rank >= 0 && rank < c->cfg.D, REALB_EINVAL, "rank=%d outside [0,%d)", rank, c->cfg.D);
@@ -274,17 +278,13 @@ int route_and_index(Ctx* c, const float* logits, const uint8_t* is_vision, int T
     const int n_part = route_topk_only(c, logits, is_vision, T, topk_ids, topk_w, s);
     if (n_part < 0) return n_part;
     const int n_chunks = ceil_div(A, kPermChunk);
+    const int n_groups = ceil_div(n_chunks, kGroup);
     const int lo = rank * n_local;
-    const int chunk_blocks = ceil_div(n_chunks, 4);
-    hipLaunchKernelGGL(reduce_and_count_kernel, dim3(1 + ceil_div(n_chunks, 16)), dim3(1024), 2 * (size_t)E * sizeof(int32_t), s,
-                       c->hist_part, n_part, E, D, expert_cnt, expert_vis, rank_load, rank_vis, c->stats_host, topk_ids, (int)A, lo,
-                       n_local, n_chunks, c->wave_cnt);
-    REALB_HIP(hipGetLastError());
-    REALB_HIP(hipEventRecord(stats_ready, s));
-    hipLaunchKernelGGL(perm_scan_kernel, dim3(1), dim3(1024), 0, s, c->wave_cnt, n_chunks, n_local, expert_offsets);
-    if (n_chunks > 0)
-        hipLaunchKernelGGL(perm_rank_kernel, dim3(chunk_blocks), dim3(256), 0, s, topk_ids, (int)A, lo, n_local, n_chunks,
-                           c->wave_cnt, expert_offsets, row_to_assign, assign_to_row);
+    hipLaunchKernelGGL(reduce_and_count_kernel, dim3(1 + n_groups), dim3(64 * kGroup), 2 * (size_t)E * sizeof(int32_t), s,
+                       c->hist_part, n_part, E, D, expert_cnt, expert_vis, rank_load, rank_vis, c->stats_words, stats_seq, topk_ids,
+                       (int)A, lo, n_local, n_chunks, n_groups, c->wave_cnt, c->group_cnt);
+    hipLaunchKernelGGL(perm_rank_kernel, dim3(n_groups > 0 ? n_groups : 1), dim3(64 * kGroup), 0, s, topk_ids, (int)A, lo, n_local,
+                       n_chunks, n_groups, c->wave_cnt, c->group_cnt, expert_offsets, row_to_assign, assign_to_row);
     REALB_HIP(hipGetLastError());
     return REALB_OK;
 }

@@ -185,10 +185,9 @@ __global__ void __launch_bounds__(1024, 2) topk_hist_rows_kernel(const float* __
 
 __global__ void __launch_bounds__(1024) hist_reduce_kernel(const int32_t* __restrict__ hist_part, int n_part, int E, int D,
                                                            int32_t* __restrict__ expert_cnt, int32_t* __restrict__ expert_vis,
-                                                           int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis,
-                                                           int32_t* __restrict__ stats_host) {
+                                                           int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis) {
     extern __shared__ int32_t tot[];                  // [2*E]
-    hist_reduce_body(tot, hist_part, n_part, E, D, expert_cnt, expert_vis, rank_load, rank_vis, stats_host);
+    hist_reduce_body(tot, hist_part, n_part, E, D, expert_cnt, expert_vis, rank_load, rank_vis, nullptr, 0);
 }
 
 // Launches the top-k + histogram kernel; returns the number of blocks (= partial histograms written).
@@ -230,13 +229,13 @@ static int launch_topk(int num_cus, int max_blocks, int32_t* hist_part, const fl
     return blocks;
 }
 
-// The top-k + histogram kernel and the reduce.  stats_host (pinned host memory) may be NULL.
-static int launch_route_stats(int num_cus, int max_blocks, int32_t* hist_part, int32_t* stats_host, const float* logits,
+// The top-k + histogram kernel and the reduce.
+static int launch_route_stats(int num_cus, int max_blocks, int32_t* hist_part, const float* logits,
                               const uint8_t* is_vision, int T, int E, int k, int D, int32_t* topk_ids, float* topk_w,
                               int32_t* expert_cnt, int32_t* expert_vis, int32_t* rank_load, int32_t* rank_vis, hipStream_t s) {
     const int blocks = launch_topk(num_cus, max_blocks, hist_part, logits, is_vision, T, E, k, topk_ids, topk_w, s);
     hipLaunchKernelGGL(hist_reduce_kernel, dim3(1), dim3(1024), 2 * (size_t)E * sizeof(int32_t), s, hist_part, blocks, E, D,
-                       expert_cnt, expert_vis, rank_load, rank_vis, stats_host);
+                       expert_cnt, expert_vis, rank_load, rank_vis);
     REALB_HIP(hipGetLastError());
     return REALB_OK;
 }
@@ -295,7 +294,7 @@ extern "C" int realb_route_stats(realb_ctx* ctx, const float* logits, const uint
     Ctx* c = reinterpret_cast<Ctx*>(ctx);
     REALB_REQUIRE(T >= 0 && T <= c->cfg.T_max, REALB_ECAP, "T=%d outside [0, T_max=%d]", T, c->cfg.T_max);
     REALB_REQUIRE(T == 0 || (logits && is_vision && topk_ids && topk_w), REALB_EINVAL, "NULL argument");
-    return launch_route_stats(c->num_cus, kRouteBlocksMax, c->hist_part, c->stats_host, logits, is_vision, T, c->cfg.E, c->cfg.k,
+    return launch_route_stats(c->num_cus, kRouteBlocksMax, c->hist_part, logits, is_vision, T, c->cfg.E, c->cfg.k,
                               c->cfg.D, topk_ids, topk_w, expert_cnt, expert_vis, rank_load, rank_vis, as_stream(stream));
 }
 
@@ -315,6 +314,6 @@ extern "C" int realb_route_stats_static(const float* logits, const uint8_t* is_v
     // every block overwrites its whole slice of the array and the reduce reads only the slices of this launch,
     // so nothing has to be cleared between calls
     const int max_blocks = (int)(kStaticCounters / (2 * (size_t)E)) < kStaticBlocksMax ? (int)(kStaticCounters / (2 * (size_t)E)) : kStaticBlocksMax;
-    return launch_route_stats(num_cus, max_blocks, part, nullptr, logits, is_vision, T, E, k, D, topk_ids, topk_w, expert_cnt,
+    return launch_route_stats(num_cus, max_blocks, part, logits, is_vision, T, E, k, D, topk_ids, topk_w, expert_cnt,
                               expert_vis, rank_load, rank_vis, as_stream(stream));
 }
