@@ -47,9 +47,12 @@ static int rank_forward_steps(realb_ctx* ctx, realb_layer_io* io, int prec, void
     if (rc != REALB_OK) return rc;
     if (fp4) REALB_REQUIRE(io->w13_q && io->w13_s && io->w2_q && io->w2_s && io->x_q && io->x_s && io->h_s, REALB_EINVAL, "NULL FP4 buffer");
     const bool prefetch = io->next_w13 != nullptr;       // cross-layer prefetch of the NEXT layer's weights, beside this layer's GEMMs
-    // weights encoded by the previous call's prefetch: everything this call enqueues from here on comes after it
+    // weights encoded by the previous call's prefetch: everything this call enqueues from here on comes after it.
+    // With the activations in flight on the side stream no wait of its own is needed (each cross-stream wait costs the
+    // caller's stream microseconds): their encoding was issued behind that prefetch on the same stream, and this call
+    // waits for it (ev_join) whatever the precision (the next prefetch goes to that same stream, behind both).
     if (c->prefetch_pending && (io->overlap == 4 || prefetch)) {
-        REALB_HIP(hipStreamWaitEvent(s, c->ev_prefetch, 0));
+        if (!act_in_flight) REALB_HIP(hipStreamWaitEvent(s, c->ev_prefetch, 0));
         c->prefetch_pending = false;
     }
     const bool encoded = io->overlap == 2 || io->overlap == 4;
