@@ -1,5 +1,5 @@
 // One-block reduction of the routing kernel's per-block partial histograms, shared by the stand-alone
-// reduce kernel and by the layer call's fused reduce + scan launch.
+// reduce kernel and by the layer call's fused reduce + count launch.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>

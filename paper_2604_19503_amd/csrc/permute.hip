@@ -237,7 +237,7 @@ using namespace realb;
 
 namespace realb {
 
-// The two halves of realb_permute.  The index half (count / scan / rank) does not depend on the
+// The two halves of realb_permute.  The index half (count / rank) does not depend on the
 // precision, so the layer can run it while the host is still taking the precision decision.
 int permute_indices(Ctx* c, const int32_t* topk_ids, int T, int rank, long long max_rows, int32_t* expert_offsets,
                     int32_t* row_to_assign, int32_t* assign_to_row, hipStream_t s) {

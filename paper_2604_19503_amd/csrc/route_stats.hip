@@ -240,7 +240,7 @@ static int launch_route_stats(int num_cus, int max_blocks, int32_t* hist_part, c
     return REALB_OK;
 }
 
-// Routing for the layer call: only the top-k + histogram kernel; the reduce is fused with the permutation's scan
+// Routing for the layer call: only the top-k + histogram kernel; the reduce is fused with the permutation's count kernel
 // (route_and_index in permute.hip).  Returns the number of partial histograms, or a negative error code.
 int route_topk_only(Ctx* c, const float* logits, const uint8_t* is_vision, int T, int32_t* topk_ids, float* topk_w, hipStream_t s) {
     REALB_REQUIRE(T >= 0 && T <= c->cfg.T_max, REALB_ECAP, "T=%d outside [0, T_max=%d]", T, c->cfg.T_max);
