@@ -70,9 +70,9 @@ __global__ void __launch_bounds__(64 * kGroup) perm_count_kernel(const int32_t* 
     perm_count_body(gsum, blockIdx.x, topk_ids, A, lo, n_local, n_chunks, n_groups, wave_cnt, group_cnt);
 }
 
-// The layer call's histogram reduce shares a launch with the permutation's count kernel: block 0 adds up the routing
-// kernel's partial histograms (and hands the per-rank statistics to the host), the other blocks count their groups of
-// chunks.  One kernel boundary less on a path made of short, latency-bound kernels.
+// The layer call's histogram reduce shares a launch with the permutation's count kernel: the first D blocks add up the
+// routing kernel's partial histograms, one EP rank each (and hand the per-rank statistics to the host), the other
+// blocks count their groups of chunks.  One kernel boundary less on a path made of short, latency-bound kernels.
 __global__ void __launch_bounds__(64 * kGroup) reduce_and_count_kernel(const int32_t* __restrict__ hist_part, int n_part, int E, int D,
                                                                         int32_t* __restrict__ expert_cnt, int32_t* __restrict__ expert_vis,
                                                                         int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis,
@@ -80,10 +80,11 @@ __global__ void __launch_bounds__(64 * kGroup) reduce_and_count_kernel(const int
                                                                         const int32_t* __restrict__ topk_ids,
                                                                         int A, int lo, int n_local, int n_chunks, int n_groups,
                                                                         int32_t* __restrict__ wave_cnt, int32_t* __restrict__ group_cnt) {
-    extern __shared__ int32_t dyn[];                  // 2*E ints (block 0 only)
+    extern __shared__ int32_t dyn[];                  // 2*E/D ints (reduce blocks only)
     __shared__ int gsum[64];
-    if (blockIdx.x == 0) hist_reduce_body(dyn, hist_part, n_part, E, D, expert_cnt, expert_vis, rank_load, rank_vis, stats_words, stats_seq);
-    else perm_count_body(gsum, blockIdx.x - 1, topk_ids, A, lo, n_local, n_chunks, n_groups, wave_cnt, group_cnt);
+    if ((int)blockIdx.x < D)
+        hist_reduce_body(dyn, hist_part, n_part, E, D, blockIdx.x, expert_cnt, expert_vis, rank_load, rank_vis, stats_words, stats_seq);
+    else perm_count_body(gsum, blockIdx.x - D, topk_ids, A, lo, n_local, n_chunks, n_groups, wave_cnt, group_cnt);
 }
 
 // Phase 2 (same blocks): every block first works out, from the group sums, each expert's total (whose exclusive scan
@@ -280,7 +281,7 @@ int route_and_index(Ctx* c, const float* logits, const uint8_t* is_vision, int T
     const int n_chunks = ceil_div(A, kPermChunk);
     const int n_groups = ceil_div(n_chunks, kGroup);
     const int lo = rank * n_local;
-    hipLaunchKernelGGL(reduce_and_count_kernel, dim3(1 + n_groups), dim3(64 * kGroup), 2 * (size_t)E * sizeof(int32_t), s,
+    hipLaunchKernelGGL(reduce_and_count_kernel, dim3(D + n_groups), dim3(64 * kGroup), 2 * (size_t)(E / D) * sizeof(int32_t), s,
                        c->hist_part, n_part, E, D, expert_cnt, expert_vis, rank_load, rank_vis, c->stats_words, stats_seq, topk_ids,
                        (int)A, lo, n_local, n_chunks, n_groups, c->wave_cnt, c->group_cnt);
     hipLaunchKernelGGL(perm_rank_kernel, dim3(n_groups > 0 ? n_groups : 1), dim3(64 * kGroup), 0, s, topk_ids, (int)A, lo, n_local,

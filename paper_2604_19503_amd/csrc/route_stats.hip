@@ -42,7 +42,7 @@ __device__ __forceinline__ float wave_max(float v) {
 // so that among equal logits the lowest (lane, slot) is the lowest expert index.
 // k rounds of: per-lane best -> wave maximum -> lowest lane holding it wins.
 // The block's histograms live in LDS; each block writes its partial histogram to the workspace
-// (no global atomics, no pre-zeroing), and a one-block kernel adds the partials up.
+// (no global atomics, no pre-zeroing), and a small kernel (one block per EP rank) adds the partials up.
 template <int EPL>
 __global__ void __launch_bounds__(1024, 2) topk_hist_kernel(const float* __restrict__ logits, const uint8_t* __restrict__ is_vision,
                                                         int T, int E, int k, int32_t* __restrict__ topk_ids,
@@ -187,7 +187,7 @@ __global__ void __launch_bounds__(1024) hist_reduce_kernel(const int32_t* __rest
                                                            int32_t* __restrict__ expert_cnt, int32_t* __restrict__ expert_vis,
                                                            int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis) {
     extern __shared__ int32_t tot[];                  // [2*E]
-    hist_reduce_body(tot, hist_part, n_part, E, D, expert_cnt, expert_vis, rank_load, rank_vis, nullptr, 0);
+    hist_reduce_body(tot, hist_part, n_part, E, D, blockIdx.x, expert_cnt, expert_vis, rank_load, rank_vis, nullptr, 0);
 }
 
 // Launches the top-k + histogram kernel; returns the number of blocks (= partial histograms written).
@@ -234,7 +234,7 @@ static int launch_route_stats(int num_cus, int max_blocks, int32_t* hist_part, c
                               const uint8_t* is_vision, int T, int E, int k, int D, int32_t* topk_ids, float* topk_w,
                               int32_t* expert_cnt, int32_t* expert_vis, int32_t* rank_load, int32_t* rank_vis, hipStream_t s) {
     const int blocks = launch_topk(num_cus, max_blocks, hist_part, logits, is_vision, T, E, k, topk_ids, topk_w, s);
-    hipLaunchKernelGGL(hist_reduce_kernel, dim3(1), dim3(1024), 2 * (size_t)E * sizeof(int32_t), s, hist_part, blocks, E, D,
+    hipLaunchKernelGGL(hist_reduce_kernel, dim3(D), dim3(1024), 2 * (size_t)(E / D) * sizeof(int32_t), s, hist_part, blocks, E, D,
                        expert_cnt, expert_vis, rank_load, rank_vis);
     REALB_HIP(hipGetLastError());
     return REALB_OK;
