@@ -80,8 +80,8 @@ int realb_destroy(realb_ctx* ctx);
 const char* realb_last_error(void);
 
 /* Device memory, in bytes, that realb_create allocates for this configuration (the permutation's per-chunk
- * counters and the routing kernel's per-block partial histograms); besides it a context holds 8*D bytes of
- * pinned host memory, one stream and four events.  Host-only, no GPU needed; 0 for an unsupported shape
+ * counters and the routing kernel's per-block partial histograms); besides it a context holds 24*D bytes of
+ * pinned host memory, one stream and its events.  Host-only, no GPU needed; 0 for an unsupported shape
  * (realb_last_error says why). */
 size_t realb_workspace_bytes(const realb_config* cfg);
 
@@ -269,7 +269,9 @@ typedef struct {
  * produces the permuted rows described above.) */
 
 /* Runs the whole path for one rank on `stream`: route_stats -> select_precision
- * (host decision, one stream sync) -> [FP4 only: quantize_experts_fp4, on the
+ * (host decision: the calling thread spins until the routing statistics, which a kernel on `stream` writes to
+ * host-coherent pinned memory, have arrived -- so the call returns only after everything that preceded it on `stream`
+ * and its own routing kernels have run; an error of the stream ends the wait) -> [FP4 only: quantize_experts_fp4, on the
  * context's side stream when io->overlap, concurrent with] permute ->
  * grouped_moe_ffn -> combine.  The side stream is joined before the GEMMs.
  * With next_w13 set, the next layer's weights are encoded on the side stream beside this layer's GEMMs
