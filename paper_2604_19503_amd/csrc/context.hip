@@ -37,8 +37,8 @@ static int check_shape(const realb_config* c) {
 
 // The two device buffers of a context's workspace.
 static int n_chunks_max(const realb_config* c) { return ceil_div((long long)c->T_max * c->k, kPermChunk) + 1; }
-static size_t wave_cnt_bytes(const realb_config* c) {      // chunk counts, then the sums over groups of 16 chunks
-    return ((size_t)n_chunks_max(c) + ceil_div(n_chunks_max(c), 16)) * (c->E / c->D) * sizeof(int32_t);
+static size_t wave_cnt_bytes(const realb_config* c) {      // chunk counts, then their sums over groups of chunks
+    return ((size_t)n_chunks_max(c) + ceil_div(n_chunks_max(c), kPermGroup)) * (c->E / c->D) * sizeof(int32_t);
 }
 static size_t hist_part_bytes(const realb_config* c) { return (size_t)kRouteBlocksMax * 2 * c->E * sizeof(int32_t); }
 

@@ -10,7 +10,7 @@
 namespace realb {
 
 constexpr int kIters = kPermChunk / 64;   // 64 assignments per wave iteration
-constexpr int kGroup = 16;                // chunks (= waves) per block of the count and rank kernels
+constexpr int kGroup = kPermGroup;        // chunks (= waves) per block of the count and rank kernels
 
 // Inclusive prefix sum over the 64 lanes with DPP only: four shifts inside each row of 16 lanes, then the
 // last lane of row 0 / row 2 is added to the following row, then lane 31 to the upper half.

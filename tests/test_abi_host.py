@@ -122,8 +122,8 @@ def test_bad_force_value_is_an_error():
 def test_workspace_bytes_is_host_only_and_matches_its_definition():
     lib = R.load_library()
     cfg = binding.default_config(16384, 64, 6, 8, 2048, 1408)
-    n_chunks = -(-16384 * 6 // 256) + 1                                # chunk counts + their sums over groups of 16 chunks
-    assert binding.workspace_bytes(cfg) == (n_chunks + -(-n_chunks // 16)) * 8 * 4 + 512 * 2 * 64 * 4
+    n_chunks = -(-16384 * 6 // 256) + 1                                # chunk counts + their sums over groups of 4 chunks
+    assert binding.workspace_bytes(cfg) == (n_chunks + -(-n_chunks // 4)) * 8 * 4 + 512 * 2 * 64 * 4
     small = binding.default_config(0, 8, 2, 1, 256, 128)
     assert binding.workspace_bytes(small) == (1 + 1) * 8 * 4 + 512 * 2 * 8 * 4
     bad = binding.default_config(128, 64, 6, 7, 2048, 1408)            # E not a multiple of D
