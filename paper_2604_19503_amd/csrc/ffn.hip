@@ -248,7 +248,10 @@ __device__ __forceinline__ void epilogue_mt(const GemmParams& p, v16f_t (&a)[WN]
             if constexpr (FP4) {
                 const u32x4_t v0 = {hb[0], hb[1], hb[2], hb[3]}, v1 = {hb[4], hb[5], hb[6], hb[7]};
                 uint32_t amax = max(amax_bits8(v0), amax_bits8(v1));
-                amax = max(amax, (uint32_t)__shfl_xor((int)amax, 32));    // the block's other 16 columns
+                // the block's other 16 columns sit in lane^32: swapping the upper half of one copy with the lower half of
+                // another leaves {lo, lo} and {hi, hi}, whose maximum is the pair's -- one VALU instruction, no LDS round trip
+                const auto halves = __builtin_amdgcn_permlane32_swap(amax, amax, false, false);
+                amax = max(halves[0], halves[1]);
                 const uint32_t byte = e8m0_from_amax(amax);
                 const float scl = scale_operand(byte);
                 const u32x2_t codes = {encode8(v0, scl), encode8(v1, scl)};
