@@ -727,6 +727,14 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
 #pragma unroll
         for (int t = 0; t < 2; ++t) fb[slot][t] = *reinterpret_cast<const u32x4_t*>(st + REGION_W + b_pos[t] * KB + (f_off0 ^ (s << 5)));
     };
+    // the same reads in four parts (part 0: row tile 0 and both column tiles, part 1: row tile 1, ...)
+    auto read_frags_part = [&](int part, int s, int slot, const uint8_t* st) __attribute__((always_inline)) {
+        fa[slot][part] = *reinterpret_cast<const u32x4_t*>(st + a_base + part * 32 * KB + (f_off0 ^ (s << 5)));
+        if (part == 0) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) fb[slot][t] = *reinterpret_cast<const u32x4_t*>(st + REGION_W + b_pos[t] * KB + (f_off0 ^ (s << 5)));
+        }
+    };
     u32x2_t ra[4], rb[2];                                 // FP4: raw scale words as read from LDS
     auto read_scales = [&](int stage) __attribute__((always_inline)) {
         if constexpr (FP4) {
@@ -763,8 +771,9 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
         // one activation transfer of the producer's new step into the stage just released.
         // Slice s multiplies out of fragment slot s&1.  The fragments of the following slice (next = s+1,
         // or next = 4: the first slice of the next step, with its scales, out of the stage that has just
-        // been published) are requested right after the first row tile's MFMAs: the other slot is free by
-        // then, and the wait in front of this slice's first MFMA does not cover the new request.
+        // been published) are requested into the other slot, a quarter of them after each row tile's MFMAs
+        // (one burst of six reads behind the first row tile measured 0.5-1 % slower: the LDS also takes
+        // the transfers' writes); the wait in front of this slice's first MFMA does not cover the new requests.
         auto slice = [&](int s, int produce, bool multiply, int next) __attribute__((always_inline)) {
 #pragma unroll
             for (int mt = 0; mt < 4; ++mt) {
@@ -776,9 +785,9 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
-                if (mt == 0 && next >= 0) {
-                    if (next < 4) read_frags(next, next & 1, st);
-                    else { read_scales(stg); read_frags(0, 0, smem + stg * STAGE); }
+                if (next >= 0) {
+                    if (next < 4) read_frags_part(mt, next, next & 1, st);
+                    else { if (mt == 0) read_scales(stg); read_frags_part(mt, 0, 0, smem + stg * STAGE); }
                 }
                 if (produce == 1) {
                     if (FP4 && mt < 2) issue(mt, pk, stg ^ 1);
