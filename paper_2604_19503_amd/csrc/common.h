@@ -10,9 +10,8 @@ namespace realb {
 
 constexpr int kWave = 64;
 constexpr int kPermChunk = 256;    // assignments ranked by one wave in permute
-// Chunks (= waves) per block of the permutation's count and rank kernels.  Small blocks: these latency-bound kernels run
-// beside the HBM-bound encoders of the side stream, and a 4-wave block finds room on a busy CU much sooner than a
-// 16-wave one (measured: layer steps 1 % shorter on the 32k- and 64k-token configurations, unchanged on the 16k one).
+// Smallest group of chunks that one block of the permutation's count and rank kernels handles (the workspace holds one
+// per-expert sum per group).
 constexpr int kPermGroup = 4;
 constexpr int kRouteBlocksMax = 512;   // most blocks the routing kernel is launched with (two per CU on 256 CUs)
 

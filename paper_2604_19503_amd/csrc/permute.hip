@@ -6,11 +6,18 @@
 #include "common.h"
 #include "hist_reduce.h"
 #include "mxfp4_device.h"
+#include <type_traits>
 
 namespace realb {
 
 constexpr int kIters = kPermChunk / 64;   // 64 assignments per wave iteration
-constexpr int kGroup = kPermGroup;        // chunks (= waves) per block of the count and rank kernels
+// Chunks (= waves) per block of the count and rank kernels: kPermGroup (4) for long batches, 16 for short ones.  These
+// latency-bound kernels run beside the HBM-bound encoders of the side stream.  Measured, whole layer steps: with more than
+// about 500 chunks (32k and 64k tokens) 4-wave blocks are 1 % faster -- a small block finds room on a busy CU sooner --,
+// with fewer (16k tokens: 384 chunks, 24 blocks of 16 waves) the large blocks are, by as much in the prefetched form of
+// the call.  The workspace is sized for the small groups.
+constexpr int kGroupLong = kPermGroup, kGroupShort = 16;
+static int perm_group(int n_chunks) { return n_chunks > 512 ? kGroupLong : kGroupShort; }
 
 // Inclusive prefix sum over the 64 lanes with DPP only: four shifts inside each row of 16 lanes, then the
 // last lane of row 0 / row 2 is added to the following row, then lane 31 to the upper half.
@@ -35,15 +42,16 @@ __device__ __forceinline__ void load_chunk(int (&le)[kIters], const int32_t* __r
     }
 }
 
-// Phase 1 (a block = one group of kGroup chunks, one wave per chunk): each wave counts, per local expert, the
+// Phase 1 (a block = one group of G chunks, one wave per chunk): each wave counts, per local expert, the
 // assignments of its chunk of kPermChunk consecutive flat indices (lane e holds expert e's count); the block adds
 // them up per expert.  wave_cnt is expert-major [n_local, n_chunks], group_cnt [n_local, n_groups].
 // gsum: 64 ints of LDS.
+template <int G>
 __device__ __forceinline__ void perm_count_body(int* gsum, int group, const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
                                                 int n_chunks, int n_groups, int32_t* __restrict__ wave_cnt,
                                                 int32_t* __restrict__ group_cnt) {
     const int lane = threadIdx.x & 63;
-    const int chunk = group * kGroup + (threadIdx.x >> 6);
+    const int chunk = group * G + (threadIdx.x >> 6);
     int le[kIters];
     load_chunk(le, topk_ids, chunk, n_chunks, A, lo, lane);
     if (threadIdx.x < 64) gsum[threadIdx.x] = 0;
@@ -63,17 +71,19 @@ __device__ __forceinline__ void perm_count_body(int* gsum, int group, const int3
     if ((int)threadIdx.x < n_local) group_cnt[(size_t)threadIdx.x * n_groups + group] = gsum[threadIdx.x];
 }
 
-__global__ void __launch_bounds__(64 * kGroup) perm_count_kernel(const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
+template <int G>
+__global__ void __launch_bounds__(64 * G) perm_count_kernel(const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
                                                                   int n_chunks, int n_groups, int32_t* __restrict__ wave_cnt,
                                                                   int32_t* __restrict__ group_cnt) {
     __shared__ int gsum[64];
-    perm_count_body(gsum, blockIdx.x, topk_ids, A, lo, n_local, n_chunks, n_groups, wave_cnt, group_cnt);
+    perm_count_body<G>(gsum, blockIdx.x, topk_ids, A, lo, n_local, n_chunks, n_groups, wave_cnt, group_cnt);
 }
 
 // The layer call's histogram reduce shares a launch with the permutation's count kernel: the first D blocks add up the
 // routing kernel's partial histograms, one EP rank each (and hand the per-rank statistics to the host), the other
 // blocks count their groups of chunks.  One kernel boundary less on a path made of short, latency-bound kernels.
-__global__ void __launch_bounds__(64 * kGroup) reduce_and_count_kernel(const int32_t* __restrict__ hist_part, int n_part, int E, int D,
+template <int G>
+__global__ void __launch_bounds__(64 * G) reduce_and_count_kernel(const int32_t* __restrict__ hist_part, int n_part, int E, int D,
                                                                         int32_t* __restrict__ expert_cnt, int32_t* __restrict__ expert_vis,
                                                                         int32_t* __restrict__ rank_load, int32_t* __restrict__ rank_vis,
                                                                         unsigned long long* __restrict__ stats_words, int stats_seq,
@@ -84,7 +94,7 @@ __global__ void __launch_bounds__(64 * kGroup) reduce_and_count_kernel(const int
     __shared__ int gsum[64];
     if ((int)blockIdx.x < D)
         hist_reduce_body(dyn, hist_part, n_part, E, D, blockIdx.x, expert_cnt, expert_vis, rank_load, rank_vis, stats_words, stats_seq);
-    else perm_count_body(gsum, blockIdx.x - D, topk_ids, A, lo, n_local, n_chunks, n_groups, wave_cnt, group_cnt);
+    else perm_count_body<G>(gsum, blockIdx.x - D, topk_ids, A, lo, n_local, n_chunks, n_groups, wave_cnt, group_cnt);
 }
 
 // Phase 2 (same blocks): every block first works out, from the group sums, each expert's total (whose exclusive scan
@@ -92,7 +102,8 @@ __global__ void __launch_bounds__(64 * kGroup) reduce_and_count_kernel(const int
 // adds up expert w's column of group_cnt, 64 groups per step -- so no separate scan kernel sits between the two
 // phases.  Then each wave walks its chunk again and gives every local assignment its row:
 // expert_offsets[e] + (assignments of e in earlier groups) + (in earlier chunks of the group) + (rank inside the chunk).
-__global__ void __launch_bounds__(64 * kGroup) perm_rank_kernel(const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
+template <int G>
+__global__ void __launch_bounds__(64 * G) perm_rank_kernel(const int32_t* __restrict__ topk_ids, int A, int lo, int n_local,
                                                                  int n_chunks, int n_groups, const int32_t* __restrict__ wave_cnt,
                                                                  const int32_t* __restrict__ group_cnt,
                                                                  int32_t* __restrict__ expert_offsets,
@@ -100,20 +111,20 @@ __global__ void __launch_bounds__(64 * kGroup) perm_rank_kernel(const int32_t* _
     __shared__ int before[64], total[64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int group = blockIdx.x;
-    const int chunk = group * kGroup + wave;
+    const int chunk = group * G + wave;
     int le[kIters];
     load_chunk(le, topk_ids, chunk, n_chunks, A, lo, lane);
     // this lane's expert: its assignments in the earlier chunks of this group
     int within = 0;
     if (lane < n_local) {
-        int v[kGroup];
+        int v[G];
 #pragma unroll
-        for (int q = 0; q < kGroup; ++q)                     // (q < wave: chunk group*kGroup + q exists whenever this wave's chunk does)
-            v[q] = (q < wave && group * kGroup + q < n_chunks) ? wave_cnt[(size_t)lane * n_chunks + group * kGroup + q] : 0;
+        for (int q = 0; q < G; ++q)                          // (q < wave: chunk group*G + q exists whenever this wave's chunk does)
+            v[q] = (q < wave && group * G + q < n_chunks) ? wave_cnt[(size_t)lane * n_chunks + group * G + q] : 0;
 #pragma unroll
-        for (int q = 0; q < kGroup; ++q) within += v[q];
+        for (int q = 0; q < G; ++q) within += v[q];
     }
-    for (int e = wave; e < n_local; e += kGroup) {
+    for (int e = wave; e < n_local; e += G) {
         int b = 0, t = 0;
         for (int q = lane; q < n_groups; q += 64) {
             const int v = group_cnt[(size_t)e * n_groups + q];
@@ -251,13 +262,19 @@ int permute_indices(Ctx* c, const int32_t* topk_ids, int T, int rank, long long 
     REALB_REQUIRE(max_rows >= worst, REALB_EINVAL, "max_rows=%lld is below the worst case %lld", max_rows, worst);
     REALB_REQUIRE(T == 0 || (topk_ids && row_to_assign && assign_to_row), REALB_EINVAL, "NULL argument");
     const int n_chunks = ceil_div(A, kPermChunk);
-    const int n_groups = ceil_div(n_chunks, kGroup);
+    const int G = perm_group(n_chunks);
+    const int n_groups = ceil_div(n_chunks, G);
     const int lo = rank * n_local;
-    if (n_groups > 0)
-        hipLaunchKernelGGL(perm_count_kernel, dim3(n_groups), dim3(64 * kGroup), 0, s, topk_ids, (int)A, lo, n_local, n_chunks, n_groups,
-                           c->wave_cnt, c->group_cnt);
-    hipLaunchKernelGGL(perm_rank_kernel, dim3(n_groups > 0 ? n_groups : 1), dim3(64 * kGroup), 0, s, topk_ids, (int)A, lo, n_local,
-                       n_chunks, n_groups, c->wave_cnt, c->group_cnt, expert_offsets, row_to_assign, assign_to_row);
+    auto launch = [&](auto g) {
+        constexpr int GG = decltype(g)::value;
+        if (n_groups > 0)
+            hipLaunchKernelGGL(perm_count_kernel<GG>, dim3(n_groups), dim3(64 * GG), 0, s, topk_ids, (int)A, lo, n_local, n_chunks,
+                               n_groups, c->wave_cnt, c->group_cnt);
+        hipLaunchKernelGGL(perm_rank_kernel<GG>, dim3(n_groups > 0 ? n_groups : 1), dim3(64 * GG), 0, s, topk_ids, (int)A, lo, n_local,
+                           n_chunks, n_groups, c->wave_cnt, c->group_cnt, expert_offsets, row_to_assign, assign_to_row);
+    };
+    if (G == kGroupLong) launch(std::integral_constant<int, kGroupLong>{});
+    else launch(std::integral_constant<int, kGroupShort>{});
     REALB_HIP(hipGetLastError());
     return REALB_OK;
 }
@@ -279,13 +296,19 @@ int route_and_index(Ctx* c, const float* logits, const uint8_t* is_vision, int T
     const int n_part = route_topk_only(c, logits, is_vision, T, topk_ids, topk_w, s);
     if (n_part < 0) return n_part;
     const int n_chunks = ceil_div(A, kPermChunk);
-    const int n_groups = ceil_div(n_chunks, kGroup);
+    const int G = perm_group(n_chunks);
+    const int n_groups = ceil_div(n_chunks, G);
     const int lo = rank * n_local;
-    hipLaunchKernelGGL(reduce_and_count_kernel, dim3(D + n_groups), dim3(64 * kGroup), 2 * (size_t)(E / D) * sizeof(int32_t), s,
-                       c->hist_part, n_part, E, D, expert_cnt, expert_vis, rank_load, rank_vis, c->stats_words, stats_seq, topk_ids,
-                       (int)A, lo, n_local, n_chunks, n_groups, c->wave_cnt, c->group_cnt);
-    hipLaunchKernelGGL(perm_rank_kernel, dim3(n_groups > 0 ? n_groups : 1), dim3(64 * kGroup), 0, s, topk_ids, (int)A, lo, n_local,
-                       n_chunks, n_groups, c->wave_cnt, c->group_cnt, expert_offsets, row_to_assign, assign_to_row);
+    auto launch = [&](auto g) {
+        constexpr int GG = decltype(g)::value;
+        hipLaunchKernelGGL(reduce_and_count_kernel<GG>, dim3(D + n_groups), dim3(64 * GG), 2 * (size_t)(E / D) * sizeof(int32_t), s,
+                           c->hist_part, n_part, E, D, expert_cnt, expert_vis, rank_load, rank_vis, c->stats_words, stats_seq, topk_ids,
+                           (int)A, lo, n_local, n_chunks, n_groups, c->wave_cnt, c->group_cnt);
+        hipLaunchKernelGGL(perm_rank_kernel<GG>, dim3(n_groups > 0 ? n_groups : 1), dim3(64 * GG), 0, s, topk_ids, (int)A, lo, n_local,
+                           n_chunks, n_groups, c->wave_cnt, c->group_cnt, expert_offsets, row_to_assign, assign_to_row);
+    };
+    if (G == kGroupLong) launch(std::integral_constant<int, kGroupLong>{});
+    else launch(std::integral_constant<int, kGroupShort>{});
     REALB_HIP(hipGetLastError());
     return REALB_OK;
 }
