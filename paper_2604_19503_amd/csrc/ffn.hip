@@ -745,6 +745,16 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
             for (int t = 0; t < 2; ++t) rb[t] = *reinterpret_cast<const u32x2_t*>(sc + SC_W + (b_pos[t] + li) * 8);
         }
     };
+    auto read_scales_part = [&](int part, int stage) __attribute__((always_inline)) {   // the same in four parts, like the fragments
+        if constexpr (FP4) {
+            const uint8_t* sc = smem + SC_BASE + stage * SC_STAGE;
+            ra[part] = *reinterpret_cast<const u32x2_t*>(sc + (wm * 128 + part * 32 + li) * 8);
+            if (part == 0) {
+#pragma unroll
+                for (int t = 0; t < 2; ++t) rb[t] = *reinterpret_cast<const u32x2_t*>(sc + SC_W + (b_pos[t] + li) * 8);
+            }
+        }
+    };
     auto take_scales = [&]() __attribute__((always_inline)) {     // this lane's byte pair of each word (op_sel picks the byte)
 #pragma unroll
         for (int mt = 0; mt < 4; ++mt) {
@@ -787,7 +797,7 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
                 __builtin_amdgcn_sched_barrier(0);
                 if (next >= 0) {
                     if (next < 4) read_frags_part(mt, next, next & 1, st);
-                    else { if (mt == 0) read_scales(stg); read_frags_part(mt, 0, 0, smem + stg * STAGE); }
+                    else { read_scales_part(mt, stg); read_frags_part(mt, 0, 0, smem + stg * STAGE); }
                 }
                 if (produce == 1) {
                     if (FP4 && mt < 2) issue(mt, pk, stg ^ 1);
