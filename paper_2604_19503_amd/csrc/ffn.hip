@@ -590,7 +590,8 @@ __global__ void __launch_bounds__(512, 1) ffn_gemm256_kernel(const GemmParams p)
     const int I_up = p.w_rows >> 1;
     const uint32_t rowbytes = FP4 ? (uint32_t)(p.K >> 1) : (uint32_t)p.K * 2;
     const int nks = (int)((rowbytes + KB - 1) / KB);
-    const bool tail_half = (rowbytes % KB) != 0;          // last K-step holds 64 bytes per row
+    // last K-step holds 64 bytes per row: FP4 rows only (K is a multiple of 128 values, so a BF16 row is whole K-steps)
+    const bool tail_half = FP4 && (rowbytes % KB) != 0;
     const int kd = p.K >> 7;                              // FP4: scale dwords per row
 
     // ---- consumer side: fragment offsets inside a stage
